@@ -1,0 +1,188 @@
+/*
+ * fp64 CPU oracle for multi-head attention forward and backward.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * HIP kernels are checked against.  It shares no code, header, table or helper
+ * with the GPU path, and the GPU path never calls it.  Only the tests, the
+ * smoke check and the benchmark's cpu_baseline leg may load it.
+ *
+ * What it computes, per (batch, head) independently, for row-major N x d
+ * matrices Q, K, V (paper Sec. 2.1, Eq. 1, with the scale applied to the logits
+ * before the softmax, which is the only reading under which rows of P sum to
+ * one and which every system the paper compares against computes):
+ *
+ *   S_ij   = scale * sum_k Q_ik K_jk                       (Eq. 1, first line)
+ *   causal : keys j > i are excluded (S_ij = -inf)         (Sec. 2.1, masked MHA)
+ *   m_i    = max_j S_ij,  f_ij = exp(S_ij - m_i),
+ *   l_i    = sum_j f_ij,  P_ij = f_ij / l_i                (Sec. 3.2.1, Eq. 2, with
+ *                                                           l = sum of f, the only
+ *                                                           reading for which the
+ *                                                           merge rule of Eq. 3 holds)
+ *   LSE_i  = m_i + ln l_i    (the row statistic the forward saves for the
+ *                             backward; Sec. 3.3 uses it as Exp(S_ij - L_i) = P_ij,
+ *                             which holds only for the log-sum-exp)
+ *   O_ik   = sum_j P_ij V_jk                               (Eq. 1, third line)
+ *
+ * Backward (Sec. 3.3, Eq. 4), given dO:
+ *   D_i    = sum_k dO_ik O_ik           ("dPsum", with this oracle's own fp64 O)
+ *   dV_jk  = sum_i P_ij dO_ik           (dV = P^T dO)
+ *   dP_ij  = sum_k dO_ik V_jk           (dP = dO V^T)
+ *   dS_ij  = P_ij (dP_ij - D_i)         (Jacobian-vector product of row softmax;
+ *                                        sum_j P_ij dP_ij = D_i follows from O = P V)
+ *   dQ_ik  = scale * sum_j dS_ij K_jk   (dQ = dS K)
+ *   dK_jk  = scale * sum_i dS_ij Q_ik   (dK = dS^T Q; the printed "Q dS^T" has
+ *                                        no consistent shape)
+ *
+ * The N x N matrices are materialised per head.  There is no tiling, no online
+ * softmax, no fusion: a reader can check every loop against the formulas above.
+ * OpenMP only spreads independent rows (or independent output rows) over
+ * threads; it reorders no sum.
+ */
+#include <math.h>
+#include <stdlib.h>
+#include <stddef.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+/* S and P for one head.  P is N x N row-major; masked entries are exactly 0. */
+static void head_softmax(const double *Q, const double *K, int N, int d,
+                         double scale, int causal, double *P, double *LSE) {
+#pragma omp parallel for schedule(dynamic, 8)
+  for (int i = 0; i < N; ++i) {
+    double *Pi = P + (size_t)i * N;
+    const int jend = causal ? i + 1 : N;
+    double m = -INFINITY;
+    for (int j = 0; j < jend; ++j) {
+      double s = 0.0;
+      for (int k = 0; k < d; ++k) s += Q[(size_t)i * d + k] * K[(size_t)j * d + k];
+      s *= scale;
+      Pi[j] = s;
+      if (s > m) m = s;
+    }
+    double l = 0.0;
+    for (int j = 0; j < jend; ++j) {
+      Pi[j] = exp(Pi[j] - m);
+      l += Pi[j];
+    }
+    for (int j = 0; j < jend; ++j) Pi[j] /= l;
+    for (int j = jend; j < N; ++j) Pi[j] = 0.0;
+    LSE[i] = m + log(l);
+  }
+}
+
+/* O = P V for one head. */
+static void head_pv(const double *P, const double *V, int N, int d, double *O) {
+#pragma omp parallel for schedule(dynamic, 8)
+  for (int i = 0; i < N; ++i) {
+    double *Oi = O + (size_t)i * d;
+    for (int k = 0; k < d; ++k) Oi[k] = 0.0;
+    for (int j = 0; j < N; ++j) {
+      const double p = P[(size_t)i * N + j];
+      if (p == 0.0) continue; /* masked or underflowed: contributes exactly 0 */
+      for (int k = 0; k < d; ++k) Oi[k] += p * V[(size_t)j * d + k];
+    }
+  }
+}
+
+/*
+ * Forward for B*H heads.  Q, K, V: [B*H][N][d] fp64 (the caller widens the
+ * 16-bit inputs exactly).  Outputs O [B*H][N][d], LSE [B*H][N].  P_out, if not
+ * NULL, receives the full probability matrices [B*H][N][N] (tests only).
+ * Returns 0, or -1 on allocation failure / bad arguments.
+ */
+int oracle_mha_fwd(const double *Q, const double *K, const double *V, double *O,
+                   double *LSE, double *P_out, int BH, int N, int d,
+                   double scale, int causal) {
+  if (!Q || !K || !V || !O || !LSE || BH < 0 || N <= 0 || d <= 0) return -1;
+  double *Pbuf = P_out ? NULL : (double *)malloc((size_t)N * N * sizeof(double));
+  if (!P_out && !Pbuf) return -1;
+  for (int h = 0; h < BH; ++h) {
+    const size_t off = (size_t)h * N * d;
+    double *P = P_out ? P_out + (size_t)h * N * N : Pbuf;
+    head_softmax(Q + off, K + off, N, d, scale, causal, P, LSE + (size_t)h * N);
+    head_pv(P, V + off, N, d, O + off);
+  }
+  free(Pbuf);
+  return 0;
+}
+
+/*
+ * Backward for B*H heads.  Recomputes the forward in fp64 itself (its own O
+ * feeds D), then applies Eq. 4.  Outputs dQ, dK, dV [B*H][N][d]; also returns
+ * O and LSE if the pointers are not NULL, and D [B*H][N] if D_out is not NULL.
+ */
+int oracle_mha_bwd(const double *Q, const double *K, const double *V,
+                   const double *dO, double *dQ, double *dK, double *dV,
+                   double *O_out, double *LSE_out, double *D_out, int BH, int N,
+                   int d, double scale, int causal) {
+  if (!Q || !K || !V || !dO || !dQ || !dK || !dV || BH < 0 || N <= 0 || d <= 0)
+    return -1;
+  double *P = (double *)malloc((size_t)N * N * sizeof(double));
+  double *dS = (double *)malloc((size_t)N * N * sizeof(double));
+  double *O = (double *)malloc((size_t)N * d * sizeof(double));
+  double *LSE = (double *)malloc((size_t)N * sizeof(double));
+  double *D = (double *)malloc((size_t)N * sizeof(double));
+  if (!P || !dS || !O || !LSE || !D) {
+    free(P); free(dS); free(O); free(LSE); free(D);
+    return -1;
+  }
+  for (int h = 0; h < BH; ++h) {
+    const size_t off = (size_t)h * N * d;
+    const double *Qh = Q + off, *Kh = K + off, *Vh = V + off, *dOh = dO + off;
+    head_softmax(Qh, Kh, N, d, scale, causal, P, LSE);
+    head_pv(P, Vh, N, d, O);
+    /* D_i, dP_ij, dS_ij: independent per query row i */
+#pragma omp parallel for schedule(dynamic, 8)
+    for (int i = 0; i < N; ++i) {
+      double Di = 0.0;
+      for (int k = 0; k < d; ++k) Di += dOh[(size_t)i * d + k] * O[(size_t)i * d + k];
+      D[i] = Di;
+      const int jend = causal ? i + 1 : N;
+      for (int j = 0; j < jend; ++j) {
+        double dp = 0.0;
+        for (int k = 0; k < d; ++k) dp += dOh[(size_t)i * d + k] * Vh[(size_t)j * d + k];
+        dS[(size_t)i * N + j] = P[(size_t)i * N + j] * (dp - Di);
+      }
+      for (int j = jend; j < N; ++j) dS[(size_t)i * N + j] = 0.0;
+      /* dQ_i = scale * sum_j dS_ij K_j */
+      double *dQi = dQ + off + (size_t)i * d;
+      for (int k = 0; k < d; ++k) dQi[k] = 0.0;
+      for (int j = 0; j < jend; ++j) {
+        const double ds = dS[(size_t)i * N + j];
+        for (int k = 0; k < d; ++k) dQi[k] += ds * Kh[(size_t)j * d + k];
+      }
+      for (int k = 0; k < d; ++k) dQi[k] *= scale;
+    }
+    /* dV_j = sum_i P_ij dO_i ;  dK_j = scale * sum_i dS_ij Q_i : independent per key row j */
+#pragma omp parallel for schedule(dynamic, 8)
+    for (int j = 0; j < N; ++j) {
+      double *dVj = dV + off + (size_t)j * d;
+      double *dKj = dK + off + (size_t)j * d;
+      for (int k = 0; k < d; ++k) { dVj[k] = 0.0; dKj[k] = 0.0; }
+      const int ibeg = causal ? j : 0;
+      for (int i = ibeg; i < N; ++i) {
+        const double p = P[(size_t)i * N + j];
+        const double ds = dS[(size_t)i * N + j];
+        for (int k = 0; k < d; ++k) {
+          dVj[k] += p * dOh[(size_t)i * d + k];
+          dKj[k] += ds * Qh[(size_t)i * d + k];
+        }
+      }
+      for (int k = 0; k < d; ++k) dKj[k] *= scale;
+    }
+    if (O_out) for (size_t t = 0; t < (size_t)N * d; ++t) O_out[off + t] = O[t];
+    if (LSE_out) for (int i = 0; i < N; ++i) LSE_out[(size_t)h * N + i] = LSE[i];
+    if (D_out) for (int i = 0; i < N; ++i) D_out[(size_t)h * N + i] = D[i];
+  }
+  free(P); free(dS); free(O); free(LSE); free(D);
+  return 0;
+}

@@ -1,0 +1,227 @@
+"""Pins for the fp64 CPU oracle (no GPU).
+
+Each test ties the oracle to something other than itself: closed forms,
+invariants of softmax attention, finite differences, a hand-derived rational
+example and an independent numpy/scipy evaluation of the same definitions
+(paper Eq. 1, Sec. 3.2.1 Eq. 2-3, Sec. 3.3 Eq. 4).
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+from scipy.special import logsumexp, softmax
+
+import oracle
+
+RNG = np.random.default_rng(20250212)
+
+
+def rand(*shape):
+    return RNG.standard_normal(shape)
+
+
+def numpy_attention(Q, K, V, dO, scale, causal):
+    """Independent evaluation with library matmul / softmax / logsumexp."""
+    N = Q.shape[-2]
+    S = scale * Q @ np.swapaxes(K, -1, -2)
+    if causal:
+        S = np.where(np.tril(np.ones((N, N), dtype=bool)), S, -np.inf)
+    P = softmax(S, axis=-1)
+    LSE = logsumexp(S, axis=-1)
+    O = P @ V
+    dV = np.swapaxes(P, -1, -2) @ dO
+    dP = dO @ np.swapaxes(V, -1, -2)
+    dS = P * (dP - (P * dP).sum(-1, keepdims=True))
+    dQ = scale * dS @ K
+    dK = scale * np.swapaxes(dS, -1, -2) @ Q
+    return dict(P=P, LSE=LSE, O=O, dQ=dQ, dK=dK, dV=dV)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_rows_of_P_sum_to_one(causal):
+    Q, K, V = rand(2, 3, 37, 8) * 2, rand(2, 3, 37, 8) * 2, rand(2, 3, 37, 8)
+    O, LSE, P = oracle.mha_fwd(Q, K, V, 0.3, causal, return_P=True)
+    assert np.abs(P.sum(-1) - 1).max() <= 1e-12
+    assert (P >= 0).all()
+    if causal:
+        assert np.all(np.triu(P, 1) == 0)
+
+
+def test_zero_Q_gives_uniform_attention():
+    N, d = 29, 5
+    K, V = rand(1, 2, N, d), rand(1, 2, N, d)
+    Q = np.zeros_like(K)
+    O, LSE = oracle.mha_fwd(Q, K, V, 0.7, False)
+    np.testing.assert_allclose(O, np.broadcast_to(V.mean(2, keepdims=True), V.shape), atol=1e-13)
+    np.testing.assert_allclose(LSE, math.log(N), atol=1e-13)
+    O, LSE = oracle.mha_fwd(Q, K, V, 0.7, True)
+    prefix_mean = np.cumsum(V, axis=2) / np.arange(1, N + 1)[None, None, :, None]
+    np.testing.assert_allclose(O, prefix_mean, atol=1e-13)
+    np.testing.assert_allclose(LSE, np.broadcast_to(np.log(np.arange(1, N + 1)), LSE.shape), atol=1e-13)
+
+
+def test_causal_row0_sees_only_key0():
+    Q, K, V = rand(2, 2, 16, 4), rand(2, 2, 16, 4), rand(2, 2, 16, 4)
+    scale = 0.5
+    O, LSE = oracle.mha_fwd(Q, K, V, scale, True)
+    np.testing.assert_allclose(O[:, :, 0], V[:, :, 0], atol=1e-14)
+    np.testing.assert_allclose(LSE[:, :, 0], scale * (Q[:, :, 0] * K[:, :, 0]).sum(-1), atol=1e-13)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_constant_V_rows(causal):
+    N, d = 21, 6
+    Q, K, dO = rand(1, 2, N, d), rand(1, 2, N, d), rand(1, 2, N, d)
+    v = rand(d)
+    V = np.broadcast_to(v, (1, 2, N, d)).copy()
+    g = oracle.mha_bwd(Q, K, V, dO, 0.4, causal)
+    np.testing.assert_allclose(g["O"], V, atol=1e-13)
+    assert np.abs(g["dQ"]).max() <= 1e-12
+    assert np.abs(g["dK"]).max() <= 1e-12
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_backward_sum_invariants(causal):
+    Q, K, V, dO = (rand(2, 2, 33, 8) for _ in range(4))
+    g = oracle.mha_bwd(Q, K, V, dO, 0.35, causal)
+    # rows of dS sum to zero => columns of dK sum to zero over keys
+    assert np.abs(g["dK"].sum(2)).max() <= 1e-11
+    # rows of P sum to one => sum_j dV_j = sum_i dO_i
+    np.testing.assert_allclose(g["dV"].sum(2), dO.sum(2), atol=1e-11)
+    # D = rowsum(dO * O)
+    np.testing.assert_allclose(g["D"], (dO * g["O"]).sum(-1), atol=1e-13)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_key_shift_invariance(causal):
+    N, d, scale = 24, 8, 0.3
+    Q, K, V, dO = (rand(1, 3, N, d) for _ in range(4))
+    c = rand(d) * 3
+    g0 = oracle.mha_bwd(Q, K, V, dO, scale, causal)
+    g1 = oracle.mha_bwd(Q, K + c, V, dO, scale, causal)
+    for name in ("O", "dQ", "dK", "dV"):
+        np.testing.assert_allclose(g1[name], g0[name], atol=1e-10, err_msg=name)
+    np.testing.assert_allclose(g1["LSE"] - g0["LSE"], scale * Q @ c, atol=1e-11)
+
+
+def test_key_permutation_noncausal():
+    N, d = 19, 4
+    Q, K, V, dO = (rand(1, 2, N, d) for _ in range(4))
+    perm = RNG.permutation(N)
+    g0 = oracle.mha_bwd(Q, K, V, dO, 0.5, False)
+    g1 = oracle.mha_bwd(Q, K[:, :, perm], V[:, :, perm], dO, 0.5, False)
+    np.testing.assert_allclose(g1["O"], g0["O"], atol=1e-12)
+    np.testing.assert_allclose(g1["dQ"], g0["dQ"], atol=1e-12)
+    np.testing.assert_allclose(g1["dK"], g0["dK"][:, :, perm], atol=1e-12)
+    np.testing.assert_allclose(g1["dV"], g0["dV"][:, :, perm], atol=1e-12)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_finite_difference_gradients(causal):
+    """dQ, dK, dV are the gradient of L = sum(O * dO) (central differences)."""
+    N, d, scale, h = 7, 3, 0.6, 1e-5
+    Q, K, V, dO = (rand(1, 2, N, d) for _ in range(4))
+    g = oracle.mha_bwd(Q, K, V, dO, scale, causal)
+
+    def loss(q, k, v):
+        return float((oracle.mha_fwd(q, k, v, scale, causal)[0] * dO).sum())
+
+    for name, idx in (("dQ", 0), ("dK", 1), ("dV", 2)):
+        num = np.zeros_like(Q)
+        base = [Q, K, V]
+        it = np.nditer(base[idx], flags=["multi_index"])
+        for _ in it:
+            mi = it.multi_index
+            args_p = [a.copy() for a in base]
+            args_m = [a.copy() for a in base]
+            args_p[idx][mi] += h
+            args_m[idx][mi] -= h
+            num[mi] = (loss(*args_p) - loss(*args_m)) / (2 * h)
+        err = np.abs(num - g[name]).max() / max(np.abs(g[name]).max(), 1e-30)
+        assert err <= 1e-6, (name, err)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("shape", [(1, 1, 1, 1), (2, 3, 50, 16), (1, 2, 130, 64)])
+def test_against_numpy_scipy(shape, causal):
+    Q, K, V, dO = (rand(*shape) for _ in range(4))
+    Q *= 1.7
+    scale = 1.0 / math.sqrt(shape[-1])
+    ref = numpy_attention(Q, K, V, dO, scale, causal)
+    O, LSE, P = oracle.mha_fwd(Q, K, V, scale, causal, return_P=True)
+    g = oracle.mha_bwd(Q, K, V, dO, scale, causal)
+    np.testing.assert_allclose(P, ref["P"], rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(O, ref["O"], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(LSE, ref["LSE"], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(g["O"], O, rtol=0, atol=0)
+    np.testing.assert_allclose(g["LSE"], LSE, rtol=0, atol=0)
+    for name in ("dQ", "dK", "dV"):
+        denom = np.linalg.norm(ref[name])
+        assert np.linalg.norm(g[name] - ref[name]) <= 1e-12 * max(denom, 1e-30), name
+
+
+def _parse_golden(path):
+    ln3, ln4 = math.log(3.0), math.log(4.0)
+    vals = {}
+    with open(path) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            name, *toks = line.split()
+            out = []
+            for t in toks:
+                t = t.replace("ln3", repr(ln3)).replace("ln4", repr(ln4))
+                prod = 1.0
+                for fct in t.split("*"):
+                    prod *= float(fct)
+                out.append(prod)
+            vals[name] = np.array(out)
+    return vals
+
+
+def test_hand_derived_rational_example():
+    g = _parse_golden(os.path.join(os.path.dirname(__file__), "golden", "two_key_rational.txt"))
+    scale = float(g["scale"][0])
+    sh = (1, 1, 2, 1)
+    Q, K, V, dO = (g[n].reshape(sh) for n in ("Q", "K", "V", "dO"))
+    O, LSE, P = oracle.mha_fwd(Q, K, V, scale, False, return_P=True)
+    b = oracle.mha_bwd(Q, K, V, dO, scale, False)
+    np.testing.assert_allclose(P.ravel(), g["P"], atol=1e-15)
+    np.testing.assert_allclose(O.ravel(), g["O"], atol=1e-14)
+    np.testing.assert_allclose(LSE.ravel(), g["LSE"], atol=1e-14)
+    for n in ("dQ", "dK", "dV"):
+        np.testing.assert_allclose(b[n].ravel(), g[n], atol=1e-14, err_msg=n)
+
+
+def test_blockwise_merge_rule_equals_direct_softmax():
+    """Eq. 3's merge of two blocks (with l = sum of f) reproduces the oracle's P, LSE."""
+    N, d, scale = 48, 8, 0.5
+    Q, K, V = rand(1, 1, N, d) * 2, rand(1, 1, N, d) * 2, rand(1, 1, N, d)
+    O, LSE, P = oracle.mha_fwd(Q, K, V, scale, False, return_P=True)
+    S = scale * Q[0, 0] @ K[0, 0].T
+    m = np.full(N, -np.inf)
+    l = np.zeros(N)
+    acc = np.zeros((N, d))
+    for j0 in range(0, N, 16):
+        Sb = S[:, j0:j0 + 16]
+        m_new = np.maximum(m, Sb.max(1))
+        f = np.exp(Sb - m_new[:, None])
+        alpha = np.exp(m - m_new)
+        l = alpha * l + f.sum(1)
+        acc = alpha[:, None] * acc + f @ V[0, 0, j0:j0 + 16]
+        m = m_new
+    np.testing.assert_allclose(acc / l[:, None], O[0, 0], atol=1e-13)
+    np.testing.assert_allclose(m + np.log(l), LSE[0, 0], atol=1e-13)
+
+
+def test_large_logits_do_not_overflow():
+    """Logits of magnitude ~1e3: exp(S) overflows fp64 unless the row max is subtracted."""
+    N, d = 16, 4
+    Q, K, V = rand(1, 1, N, d) * 30, rand(1, 1, N, d) * 30, rand(1, 1, N, d)
+    O, LSE, P = oracle.mha_fwd(Q, K, V, 1.0, False, return_P=True)
+    assert np.isfinite(O).all() and np.isfinite(LSE).all()
+    assert np.abs(P.sum(-1) - 1).max() <= 1e-12
+    S = Q[0, 0] @ K[0, 0].T
+    np.testing.assert_allclose(LSE[0, 0], logsumexp(S, axis=-1), rtol=1e-13)
