@@ -1,0 +1,104 @@
+/*
+ * spark_mha.h -- C ABI of the fused multi-head-attention library for MI355X (gfx950).
+ *
+ * Two operations, each enqueued on a caller-provided HIP stream:
+ *
+ *   spark_mha_fwd : O = softmax(scale * Q K^T [+ causal mask]) V, and the row
+ *                   statistic LSE that the backward needs.
+ *                   (paper Sec. 2.1 Eq. 1; fused single-kernel scheme of Sec. 3.2;
+ *                   online softmax of Sec. 3.2.1 Eq. 2-3.  The scale multiplies
+ *                   the logits before the softmax.)
+ *   spark_mha_bwd : dQ, dK, dV from dO, recomputing P = exp(S - LSE) instead of
+ *                   storing it (paper Sec. 3.3 Eq. 4, with dK = dS^T Q and
+ *                   dS = P o (dP - D), D = rowsum(dO o O), the paper's "dPsum").
+ *
+ * Conventions common to every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates, frees or synchronises; it only enqueues kernels on
+ *     `stream` (a hipStream_t passed as void*; NULL means the default stream).
+ *   - Q, K, V, O, dO, dQ, dK, dV have shape [B, H, N, d], contiguous, d fastest,
+ *     element type `dtype` (IEEE fp16 or bfloat16).  LSE has shape [B, H, N],
+ *     fp32.  Pointers must be 16-byte aligned.  Inputs and outputs must not
+ *     alias each other.
+ *   - Supported: d in {64, 128}; any N >= 1; B, H >= 1 with B*H <= 65535*... (see
+ *     SPARK_ERR_SHAPE); scale finite and > 0; causal in {0, 1}.
+ *   - causal != 0: query i attends to keys j <= i (Sec. 2.1, masked MHA).
+ *   - Arithmetic: both contractions run on fp16/bf16 MFMA with fp32
+ *     accumulation; the softmax statistics, P before packing, the O
+ *     accumulator, LSE, D and dS before packing are fp32 (Sec. 3.2.1: softmax in
+ *     16 bits is not accurate enough).  Results are rounded once to `dtype`.
+ *   - Every argument is validated before anything is enqueued: a call that
+ *     returns an error has no side effect.  Launch failures reported by the
+ *     runtime are returned as SPARK_ERR_LAUNCH.
+ *   - Thread safety: the entry points keep no mutable global state other than a
+ *     one-time per-process kernel-attribute setup; concurrent calls on different
+ *     streams are allowed as long as their output buffers differ.
+ */
+#ifndef SPARK_MHA_H_
+#define SPARK_MHA_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { SPARK_F16 = 0, SPARK_BF16 = 1 } spark_dtype_t;
+
+typedef enum {
+  SPARK_OK = 0,
+  SPARK_ERR_NULL = -1,      /* a required pointer is NULL */
+  SPARK_ERR_SHAPE = -2,     /* B, H or N < 1; d not 64/128; B*H*N*d overflows 2^31 elements per
+                               head-batch slice limits (see below); scale not finite or <= 0 */
+  SPARK_ERR_DTYPE = -3,     /* dtype is neither SPARK_F16 nor SPARK_BF16 */
+  SPARK_ERR_ALIGN = -4,     /* a pointer is not 16-byte aligned */
+  SPARK_ERR_WORKSPACE = -5, /* workspace too small (see spark_mha_bwd_workspace_bytes) */
+  SPARK_ERR_LAUNCH = -6     /* the HIP runtime refused a launch */
+} spark_status_t;
+
+/*
+ * Forward (paper Sec. 3.2, Eq. 1-3).
+ *   Q, K, V : in,  device, [B,H,N,d] dtype
+ *   O       : out, device, [B,H,N,d] dtype, fully overwritten
+ *   LSE     : out, device, [B,H,N] fp32: natural-log log-sum-exp over the allowed
+ *             keys of the scaled logits, LSE_i = ln sum_j exp(scale * q_i . k_j).
+ *             (This is the row statistic the paper's Sec. 3.3 calls "LES" and
+ *             uses as Exp(S_ij - L_i).)
+ * Limits: B*H*ceil(N/128) < 2^31 and N*d < 2^31.
+ * Returns SPARK_OK or a negative spark_status_t.
+ */
+int spark_mha_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                  int B, int H, int N, int d, float scale, int causal,
+                  spark_dtype_t dtype, void* stream);
+
+/*
+ * Bytes of device workspace spark_mha_bwd needs for this problem (holds
+ * D = rowsum(dO o O), fp32 [B,H,N]).  Returns 0 for invalid shapes.
+ */
+size_t spark_mha_bwd_workspace_bytes(int B, int H, int N, int d, spark_dtype_t dtype);
+
+/*
+ * Backward (paper Sec. 3.3, Eq. 4).
+ *   Q, K, V, O, dO : in,  device, [B,H,N,d] dtype   (O, LSE as written by spark_mha_fwd)
+ *   LSE            : in,  device, [B,H,N] fp32
+ *   dQ, dK, dV     : out, device, [B,H,N,d] dtype, fully overwritten (no need to zero)
+ *   workspace      : device scratch of at least spark_mha_bwd_workspace_bytes(...)
+ *                    bytes, 16-byte aligned; contents on return are unspecified.
+ * Enqueues, in order on `stream`: the D pre-pass, the dK/dV kernel (one
+ * workgroup per key/value tile, accumulating dK and dV on chip as in Sec. 3.3)
+ * and the dQ kernel (one workgroup per query tile; a separate deterministic pass
+ * in place of the paper's atomic adds into HBM).
+ */
+int spark_mha_bwd(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
+                  const void* dO, void* dQ, void* dK, void* dV,
+                  void* workspace, size_t workspace_bytes,
+                  int B, int H, int N, int d, float scale, int causal,
+                  spark_dtype_t dtype, void* stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char* spark_status_str(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARK_MHA_H_ */

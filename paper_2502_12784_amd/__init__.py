@@ -1,0 +1,13 @@
+"""Fused multi-head attention (forward + backward) for MI355X, behind a C ABI.
+
+``binding`` marshals torch device tensors into ``libspark_mha.so``;
+``synth`` generates the seeded synthetic workloads; ``build`` compiles the library.
+"""
+from .binding import (  # noqa: F401
+    SparkError,
+    load_library,
+    spark_mha_bwd,
+    spark_mha_bwd_workspace_bytes,
+    spark_mha_fwd,
+    status_str,
+)

@@ -1,0 +1,127 @@
+"""Thin ctypes binding of the C ABI in ``include/spark_mha.h``.
+
+Argument marshalling only: every step of the attention path runs in the HIP
+kernels of ``libspark_mha.so``.  torch is used for device memory and for the
+current stream.  There is no fallback: if the library is missing or a call
+fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libspark_mha.so")
+
+SPARK_F16 = 0
+SPARK_BF16 = 1
+
+EXPORTS = ("spark_mha_fwd", "spark_mha_bwd", "spark_mha_bwd_workspace_bytes", "spark_status_str")
+
+_lib = None
+
+
+class SparkError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("spark_mha: %s (status %d)" % (message, status))
+        self.status = status
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the in-tree shared library; build it only if it does not exist."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from .build import build_library
+        build_library()
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i, f = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    lib.spark_mha_fwd.restype = i
+    lib.spark_mha_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, f, i, i, vp]
+    lib.spark_mha_bwd_workspace_bytes.restype = ctypes.c_size_t
+    lib.spark_mha_bwd_workspace_bytes.argtypes = [i, i, i, i, i]
+    lib.spark_mha_bwd.restype = i
+    lib.spark_mha_bwd.argtypes = [vp] * 10 + [ctypes.c_size_t, i, i, i, i, f, i, i, vp]
+    lib.spark_status_str.restype = ctypes.c_char_p
+    lib.spark_status_str.argtypes = [i]
+    _lib = lib
+    return lib
+
+
+def status_str(status: int) -> str:
+    return load_library().spark_status_str(int(status)).decode()
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise SparkError(status, status_str(status))
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float16:
+        return SPARK_F16
+    if t.dtype == torch.bfloat16:
+        return SPARK_BF16
+    raise SparkError(-3, "tensors must be float16 or bfloat16")
+
+
+def _require(t, shape, dtype, name):
+    if not t.is_cuda:
+        raise ValueError("%s must be a device tensor" % name)
+    if tuple(t.shape) != tuple(shape) or t.dtype != dtype or not t.is_contiguous():
+        raise ValueError("%s must be a contiguous %s tensor of shape %s" % (name, dtype, tuple(shape)))
+
+
+def _stream_ptr():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def spark_mha_fwd(Q, K, V, scale: float, causal: bool, O=None, LSE=None):
+    """O, LSE = fused attention forward of [B,H,N,d] device tensors on the current stream."""
+    import torch
+    lib = load_library()
+    B, H, N, d = Q.shape
+    for t, n in ((Q, "Q"), (K, "K"), (V, "V")):
+        _require(t, (B, H, N, d), Q.dtype, n)
+    if O is None:
+        O = torch.empty_like(Q)
+    if LSE is None:
+        LSE = torch.empty((B, H, N), dtype=torch.float32, device=Q.device)
+    _require(O, (B, H, N, d), Q.dtype, "O")
+    _require(LSE, (B, H, N), torch.float32, "LSE")
+    _check(lib.spark_mha_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(),
+                             B, H, N, d, float(scale), int(bool(causal)), _dtype_code(Q), _stream_ptr()))
+    return O, LSE
+
+
+def spark_mha_bwd_workspace_bytes(B: int, H: int, N: int, d: int, dtype_code: int) -> int:
+    return int(load_library().spark_mha_bwd_workspace_bytes(B, H, N, d, dtype_code))
+
+
+def spark_mha_bwd(Q, K, V, O, LSE, dO, scale: float, causal: bool, dQ=None, dK=None, dV=None,
+                  workspace=None):
+    """dQ, dK, dV = fused attention backward on the current stream."""
+    import torch
+    lib = load_library()
+    B, H, N, d = Q.shape
+    for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO")):
+        _require(t, (B, H, N, d), Q.dtype, n)
+    _require(LSE, (B, H, N), torch.float32, "LSE")
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(Q) if dK is None else dK
+    dV = torch.empty_like(Q) if dV is None else dV
+    for t, n in ((dQ, "dQ"), (dK, "dK"), (dV, "dV")):
+        _require(t, (B, H, N, d), Q.dtype, n)
+    code = _dtype_code(Q)
+    need = spark_mha_bwd_workspace_bytes(B, H, N, d, code)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
+    wbytes = workspace.numel() * workspace.element_size()
+    _check(lib.spark_mha_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(),
+                             dO.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
+                             workspace.data_ptr(), wbytes, B, H, N, d, float(scale),
+                             int(bool(causal)), code, _stream_ptr()))
+    return dQ, dK, dV

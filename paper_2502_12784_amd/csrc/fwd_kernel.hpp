@@ -1,0 +1,237 @@
+// Fused attention forward for gfx950: S = scale*Q K^T, online row softmax, O = P V, LSE saved.
+//
+// Structure (paper Sec. 3.2): one workgroup owns one tile of 128 query rows of one (batch,
+// head) and loops over tiles of 64 keys; per iteration it computes the score tile on the
+// matrix cores, updates the running row max / row sum (Sec. 3.2.1, Eq. 3), rescales the O
+// accumulator by exp(m_pre - m_cur), and accumulates P V on the matrix cores.  O is written
+// once at the end, so HBM sees three reads and one write.
+//
+// What is specific to CDNA4 here:
+//   * Each of the 4 waves owns 32 query rows.  The score tile is computed TRANSPOSED,
+//     S^T = K Q^T (keys on the MFMA M axis, queries on the N axis), so a lane owns ONE query
+//     column and its 32 accumulator registers are 32 of the tile's 64 keys.  Row max and row
+//     sum are then in-lane reductions plus one exchange with the lane 32 positions away
+//     (the counterpart of the paper's shuffle step for fp32 accumulators).
+//   * O is accumulated transposed as well, O^T = V^T P^T.  The packed accumulator registers
+//     of S^T are directly the B operand of that MFMA (see mma_gfx950.hpp), and the V^T
+//     operand comes from the row-major V tile in LDS through transposing LDS reads.  P never
+//     touches LDS or HBM (the paper's Sec. 3.2.2 layout transform becomes register renaming).
+//   * K/V tiles are double-buffered in LDS; the global loads of tile j+1 are issued before the
+//     arithmetic of tile j and written to the other buffer afterwards: one barrier per tile.
+//   * Row strides in LDS are padded (K: +16 B, V: +64 B) so the 16-byte row reads of K and
+//     the 4-row transposing reads of V spread over all banks.
+#pragma once
+#include "mma_gfx950.hpp"
+
+namespace spark {
+
+template <int D> struct FwdCfg {
+  static constexpr int BM = 128;  // query rows per workgroup (32 per wave)
+  static constexpr int BN = 64;   // keys per iteration
+  static constexpr int KSTR = D * 2 + 16;
+  static constexpr int VSTR = D * 2 + 64;
+  static constexpr int KBYTES = BN * KSTR;
+  static constexpr int VBYTES = BN * VSTR;
+  static constexpr int STAGE = KBYTES + VBYTES;
+  static constexpr int OSTR = D * 2 + 16;  // epilogue staging row stride
+  static constexpr int SMEM = 2 * STAGE;
+  static_assert(4 * 32 * OSTR <= SMEM, "epilogue staging must fit in the K/V buffers");
+};
+
+// Workgroups are handed to the 8 XCDs round-robin by linear id.  Map the id so that each XCD
+// gets one contiguous range of logical work items: the query tiles of one head then share
+// that XCD's L2 for K and V.
+static __device__ __forceinline__ int xcd_contiguous(int id, int total) {
+  const int per = total >> 3, rem = total & 7;
+  const int xcd = id & 7, slot = id >> 3;
+  const int base = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
+  return base + slot;
+}
+
+template <typename T, int D, bool CAUSAL>
+__global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+    T* __restrict__ O, float* __restrict__ LSE, int N, int nqt, float scale_log2) {
+  using F = Frag<T>;
+  using v8 = typename F::v8;
+  using v4 = typename F::v4;
+  using C = FwdCfg<D>;
+  constexpr int KS = D / 16;   // k-steps of the score contraction
+  constexpr int DT = D / 32;   // 32-row tiles of O^T
+  constexpr int CPR = D / 8;   // 16-byte chunks per row
+  constexpr int NLD = C::BN * CPR / 256;  // chunks per thread per tile
+
+  extern __shared__ __attribute__((aligned(16))) char smem_generic[];
+  SPARK_LDS char* smem = (SPARK_LDS char*)smem_generic;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 5, c32 = lane & 31, i16 = lane & 15;
+
+  const int logical = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int head = logical / nqt;
+  const int rank = logical - head * nqt;
+  const int qt = CAUSAL ? nqt - 1 - rank : rank;  // causal: longest tiles first
+
+  const size_t head_off = (size_t)head * N * D;
+  const T* Qh = Q + head_off;
+  const T* Kh = K + head_off;
+  const T* Vh = V + head_off;
+
+  const int q0 = qt * C::BM + wave * 32;  // first query row of this wave
+  const int qrow = q0 + c32;              // this lane's query row
+  const int qrow_c = qrow < N ? qrow : N - 1;
+
+  v8 qf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks)
+    qf[ks] = *reinterpret_cast<const v8*>(Qh + (size_t)qrow_c * D + ks * 16 + g * 8);
+
+  int kv_end = N;
+  if (CAUSAL) {
+    const int lim = (qt + 1) * C::BM;
+    kv_end = lim < N ? lim : N;
+  }
+  const int nt = (kv_end + C::BN - 1) / C::BN;
+
+  u32x4 kreg[NLD], vreg[NLD];
+  auto load_tile = [&](int j) {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int c = tid + 256 * i;
+      const int row = c / CPR, cc = c % CPR;
+      int grow = j * C::BN + row;
+      grow = grow < N ? grow : N - 1;
+      kreg[i] = *reinterpret_cast<const u32x4*>(Kh + (size_t)grow * D + cc * 8);
+      vreg[i] = *reinterpret_cast<const u32x4*>(Vh + (size_t)grow * D + cc * 8);
+    }
+  };
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int c = tid + 256 * i;
+      const int row = c / CPR, cc = c % CPR;
+      lds_write(smem, buf * C::STAGE + row * C::KSTR + cc * 16, kreg[i]);
+      lds_write(smem, buf * C::STAGE + C::KBYTES + row * C::VSTR + cc * 16, vreg[i]);
+    }
+  };
+
+  f32x16 o[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
+  float m_run = -INFINITY;  // running row max (log2 domain)
+  float l_run = 0.f;        // running row sum over this lane's keys only (halves merged at the end)
+
+  load_tile(0);
+  store_tile(0);
+  __syncthreads();
+
+  for (int j = 0; j < nt; ++j) {
+    const int buf = j & 1;
+    if (j + 1 < nt) load_tile(j + 1);
+
+    const int k0 = j * C::BN;
+    if (!CAUSAL || k0 <= q0 + 31) {  // wave-uniform: skip tiles entirely above the diagonal
+      SPARK_LDS const char* kb = smem + buf * C::STAGE;
+      SPARK_LDS const char* vb = kb + C::KBYTES;
+
+      // S^T tile: 64 keys x 32 queries
+      f32x16 s[2];
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[mt][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+          v8 kf = lds_read16<v8>(kb, (mt * 32 + c32) * C::KSTR + ks * 32 + g * 16);
+          s[mt] = F::mfma(kf, qf[ks], s[mt]);
+        }
+      }
+
+      float t[32];
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) t[mt * 16 + r] = s[mt][r] * scale_log2;
+
+      const bool need_mask = (CAUSAL && k0 + C::BN - 1 > q0) || (k0 + C::BN > N);
+      if (need_mask) {
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = k0 + mt * 32 + 8 * (r / 4) + 4 * g + (r % 4);
+            const bool ok = key < N && (!CAUSAL || key <= qrow);
+            if (!ok) t[mt * 16 + r] = -INFINITY;
+          }
+      }
+
+      float mx = t[0];
+#pragma unroll
+      for (int i = 1; i < 32; ++i) mx = fmaxf(mx, t[i]);
+      mx = fmaxf(mx, other_half(mx));
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      m_run = m_new;
+
+      float rs = 0.f;
+#pragma unroll
+      for (int i = 0; i < 32; ++i) {
+        t[i] = __builtin_amdgcn_exp2f(t[i] - m_new);
+        rs += t[i];
+      }
+      l_run = l_run * alpha + rs;
+
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+
+      // O^T += V^T P^T, 16 keys per MFMA
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const v8 pf = pack8<T>(&t[kk * 8]);
+        const int row0 = 16 * kk + 4 * g + (i16 >> 2);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          const int col = dt * 32 + (c32 & 16) + 4 * (i16 & 3);
+          const v4 lo = lds_read_tr8<v4>(vb, row0 * C::VSTR + col * 2);
+          const v4 hi = lds_read_tr8<v4>(vb, (row0 + 8) * C::VSTR + col * 2);
+          o[dt] = F::mfma(join4<v8, v4>(lo, hi), pf, o[dt]);
+        }
+      }
+    }
+
+    if (j + 1 < nt) store_tile(buf ^ 1);
+    __syncthreads();
+  }
+
+  // Epilogue: normalise, round once, transpose through this wave's LDS slice, store rows.
+  l_run += other_half(l_run);
+  const float inv = 1.0f / l_run;
+  SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      v4 pk;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pk[e] = (T)(o[dt][r4 * 4 + e] * inv);
+      lds_write(ob, c32 * C::OSTR + (dt * 32 + 8 * r4 + 4 * g) * 2, pk);
+    }
+  T* Oh = O + head_off;
+  constexpr int RPP = 64 / CPR;  // rows per pass of the wave
+#pragma unroll
+  for (int p = 0; p < 32 / RPP; ++p) {
+    const int row = p * RPP + lane / CPR, cc = lane % CPR;
+    const u32x4 v = lds_read16<u32x4>(ob, row * C::OSTR + cc * 16);
+    if (q0 + row < N) *reinterpret_cast<u32x4*>(Oh + (size_t)(q0 + row) * D + cc * 8) = v;
+  }
+  if (g == 0 && qrow < N)
+    LSE[(size_t)head * N + qrow] = (m_run + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f;
+}
+
+}  // namespace spark

@@ -1,0 +1,91 @@
+// Wave64 MFMA fragments and LDS helpers for gfx950 (CDNA4).
+//
+// Operand layout of v_mfma_f32_32x32x16_{f16,bf16}, C[32x32] += A[32x16] * B[16x32], for lane
+// l (0..63) with g = l / 32:
+//   A : lane holds row    l % 32, k-slots 8g .. 8g+7   (8 x 16-bit, 4 VGPRs)
+//   B : lane holds column l % 32, k-slots 8g .. 8g+7
+//   C : lane holds column l % 32; register r (0..15) holds row 8*(r/4) + 4g + (r%4)
+// A contraction is invariant under one permutation applied to the k-slots of both operands.
+// The kernels use this: registers 8h..8h+7 (h = 0, 1) of a C tile, packed to 16 bits, are
+// directly a B (or A) operand whose k-slot (g, j) means row
+//     krow(h, g, j) = 16h + 8*(j/4) + 4g + (j%4)
+// of that tile, provided the other operand is gathered with the same row order.  This is the
+// CDNA4 counterpart of the paper's warp-level C->A layout transform (Sec. 3.2.2): the
+// probabilities never leave registers between the two contractions.
+//
+// ds_read_b64_tr_b16 (transposing LDS read): within each group of 16 lanes, lane i receives
+// element (i % 4) of the 4 x 16-bit words addressed by lanes 4t + i/4, t = 0..3.  For a
+// row-major tile X[row][col], lane j of the group addressing X[r0 + j/4][c0 + 4*(j%4)] makes
+// lane i receive X[r0 + t][c0 + i], t = 0..3: a column of four consecutive rows.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace spark {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+#define SPARK_LDS __attribute__((address_space(3)))
+
+template <typename T> struct Frag;
+
+template <> struct Frag<_Float16> {
+  typedef f16x8 v8;
+  typedef f16x4 v4;
+  static __device__ __forceinline__ f32x16 mfma(v8 a, v8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+  }
+};
+
+template <> struct Frag<__bf16> {
+  typedef bf16x8 v8;
+  typedef bf16x4 v4;
+  static __device__ __forceinline__ f32x16 mfma(v8 a, v8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  }
+};
+
+// 16-byte LDS read / typed LDS write at a byte offset from the start of the workgroup's LDS.
+template <typename V8>
+static __device__ __forceinline__ V8 lds_read16(SPARK_LDS const char* smem, int byte_off) {
+  return *reinterpret_cast<SPARK_LDS const V8*>(smem + byte_off);
+}
+
+template <typename V>
+static __device__ __forceinline__ void lds_write(SPARK_LDS char* smem, int byte_off, V v) {
+  *reinterpret_cast<SPARK_LDS V*>(smem + byte_off) = v;
+}
+
+// Transposing 8-byte LDS read (see the header comment); returns 4 x 16-bit.
+template <typename V4>
+static __device__ __forceinline__ V4 lds_read_tr8(SPARK_LDS const char* smem, int byte_off) {
+  i16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SPARK_LDS i16x4*)(smem + byte_off));
+  return __builtin_bit_cast(V4, v);
+}
+
+template <typename V8, typename V4>
+static __device__ __forceinline__ V8 join4(V4 lo, V4 hi) {
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// Pack 8 fp32 values to 16-bit (round to nearest even) as one MFMA operand.
+template <typename T>
+static __device__ __forceinline__ typename Frag<T>::v8 pack8(const float* x) {
+  typename Frag<T>::v8 r;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) r[i] = (T)x[i];
+  return r;
+}
+
+// Value held by the lane 32 positions away (the other half of the wave).
+static __device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32); }
+
+}  // namespace spark

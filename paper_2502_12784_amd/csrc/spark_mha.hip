@@ -1,0 +1,163 @@
+// C ABI of the fused MHA library: argument validation and kernel dispatch (host side).
+// The operations are defined in include/spark_mha.h.
+#include "../../include/spark_mha.h"
+
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "bwd_kernels.hpp"
+#include "fwd_kernel.hpp"
+
+namespace {
+
+using namespace spark;
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_common(int B, int H, int N, int d, float scale, int dtype) {
+  if (dtype != SPARK_F16 && dtype != SPARK_BF16) return SPARK_ERR_DTYPE;
+  if (B < 1 || H < 1 || N < 1) return SPARK_ERR_SHAPE;
+  if (d != 64 && d != 128) return SPARK_ERR_SHAPE;
+  if (!isfinite(scale) || !(scale > 0.f)) return SPARK_ERR_SHAPE;
+  const int64_t bh = (int64_t)B * H;
+  const int64_t tiles64 = ((int64_t)N + 63) / 64;
+  if (bh * tiles64 >= (int64_t)1 << 31) return SPARK_ERR_SHAPE;
+  if ((int64_t)N * d >= (int64_t)1 << 31) return SPARK_ERR_SHAPE;
+  return SPARK_OK;
+}
+
+template <typename KernelT>
+int set_smem(KernelT kernel, int bytes) {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  return e == hipSuccess ? SPARK_OK : SPARK_ERR_LAUNCH;
+}
+
+template <typename T, int D, bool CAUSAL>
+int launch_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int BH, int N,
+               float scale, hipStream_t st) {
+  using C = FwdCfg<D>;
+  auto kernel = mha_fwd_kernel<T, D, CAUSAL>;
+  static const int attr = set_smem(kernel, C::SMEM);
+  if (attr != SPARK_OK) return attr;
+  const int nqt = (N + C::BM - 1) / C::BM;
+  const float scale_log2 = scale * 1.4426950408889634f;
+  hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * nqt)), dim3(256), C::SMEM, st,
+                     static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
+                     static_cast<T*>(O), LSE, N, nqt, scale_log2);
+  return hipGetLastError() == hipSuccess ? SPARK_OK : SPARK_ERR_LAUNCH;
+}
+
+template <typename T, int D, bool CAUSAL>
+int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
+               const void* dO, void* dQ, void* dK, void* dV, float* Dws, int BH, int N,
+               float scale, hipStream_t st) {
+  const T* q = static_cast<const T*>(Q);
+  const T* k = static_cast<const T*>(K);
+  const T* v = static_cast<const T*>(V);
+  const T* o = static_cast<const T*>(O);
+  const T* dout = static_cast<const T*>(dO);
+  const float scale_log2 = scale * 1.4426950408889634f;
+
+  {  // D = rowsum(dO o O): one wave per 64/(D/8) rows
+    constexpr int ROWS_PER_BLOCK = 256 / (D / 8);
+    const int64_t rows = (int64_t)BH * N;
+    const unsigned grid = (unsigned)((rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK);
+    hipLaunchKernelGGL((mha_bwd_dot_kernel<T, D>), dim3(grid), dim3(256), 0, st, o, dout, Dws, rows);
+    if (hipGetLastError() != hipSuccess) return SPARK_ERR_LAUNCH;
+  }
+  {  // dK, dV: one workgroup per tile of 128 keys
+    using C = BwdKvCfg<D>;
+    auto kernel = mha_bwd_dkdv_kernel<T, D, CAUSAL>;
+    static const int attr = set_smem(kernel, C::SMEM);
+    if (attr != SPARK_OK) return attr;
+    const int nkt = (N + C::BN - 1) / C::BN;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * nkt)), dim3(256), C::SMEM, st, q, k, v, dout,
+                       LSE, Dws, static_cast<T*>(dK), static_cast<T*>(dV), N, nkt, scale,
+                       scale_log2);
+    if (hipGetLastError() != hipSuccess) return SPARK_ERR_LAUNCH;
+  }
+  {  // dQ: one workgroup per tile of 128 queries
+    using C = BwdQCfg<D>;
+    auto kernel = mha_bwd_dq_kernel<T, D, CAUSAL>;
+    static const int attr = set_smem(kernel, C::SMEM);
+    if (attr != SPARK_OK) return attr;
+    const int nqt = (N + C::BM - 1) / C::BM;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * nqt)), dim3(256), C::SMEM, st, q, k, v, dout,
+                       LSE, Dws, static_cast<T*>(dQ), N, nqt, scale, scale_log2);
+    if (hipGetLastError() != hipSuccess) return SPARK_ERR_LAUNCH;
+  }
+  return SPARK_OK;
+}
+
+// Expand the (dtype, d, causal) runtime triple into a template instantiation.
+#define SPARK_DISPATCH(FN, ...)                                                        \
+  do {                                                                                 \
+    if (dtype == SPARK_F16) {                                                          \
+      if (d == 64) return causal ? FN<_Float16, 64, true>(__VA_ARGS__)                 \
+                                 : FN<_Float16, 64, false>(__VA_ARGS__);               \
+      return causal ? FN<_Float16, 128, true>(__VA_ARGS__)                             \
+                    : FN<_Float16, 128, false>(__VA_ARGS__);                           \
+    }                                                                                  \
+    if (d == 64) return causal ? FN<__bf16, 64, true>(__VA_ARGS__)                     \
+                               : FN<__bf16, 64, false>(__VA_ARGS__);                   \
+    return causal ? FN<__bf16, 128, true>(__VA_ARGS__)                                 \
+                  : FN<__bf16, 128, false>(__VA_ARGS__);                               \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+int spark_mha_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H,
+                  int N, int d, float scale, int causal, spark_dtype_t dtype_e, void* stream) {
+  const int dtype = (int)dtype_e;
+  if (!Q || !K || !V || !O || !LSE) return SPARK_ERR_NULL;
+  const int rc = check_common(B, H, N, d, scale, dtype);
+  if (rc != SPARK_OK) return rc;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE))
+    return SPARK_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int BH = B * H;
+  SPARK_DISPATCH(launch_fwd, Q, K, V, O, LSE, BH, N, scale, st);
+}
+
+size_t spark_mha_bwd_workspace_bytes(int B, int H, int N, int d, spark_dtype_t dtype) {
+  if (check_common(B, H, N, d, 1.0f, (int)dtype) != SPARK_OK) return 0;
+  return (size_t)B * H * N * sizeof(float);
+}
+
+int spark_mha_bwd(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
+                  const void* dO, void* dQ, void* dK, void* dV, void* workspace,
+                  size_t workspace_bytes, int B, int H, int N, int d, float scale, int causal,
+                  spark_dtype_t dtype_e, void* stream) {
+  const int dtype = (int)dtype_e;
+  if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV || !workspace) return SPARK_ERR_NULL;
+  const int rc = check_common(B, H, N, d, scale, dtype);
+  if (rc != SPARK_OK) return rc;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE) ||
+      !aligned16(dO) || !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
+    return SPARK_ERR_ALIGN;
+  if (workspace_bytes < spark_mha_bwd_workspace_bytes(B, H, N, d, dtype_e))
+    return SPARK_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int BH = B * H;
+  float* Dws = static_cast<float*>(workspace);
+  SPARK_DISPATCH(launch_bwd, Q, K, V, O, LSE, dO, dQ, dK, dV, Dws, BH, N, scale, st);
+}
+
+const char* spark_status_str(int status) {
+  switch (status) {
+    case SPARK_OK: return "ok";
+    case SPARK_ERR_NULL: return "a required pointer is NULL";
+    case SPARK_ERR_SHAPE: return "unsupported shape or scale (need B,H,N >= 1, d in {64,128}, finite scale > 0)";
+    case SPARK_ERR_DTYPE: return "unsupported dtype (need SPARK_F16 or SPARK_BF16)";
+    case SPARK_ERR_ALIGN: return "a pointer is not 16-byte aligned";
+    case SPARK_ERR_WORKSPACE: return "workspace smaller than spark_mha_bwd_workspace_bytes()";
+    case SPARK_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

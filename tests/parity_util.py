@@ -1,0 +1,106 @@
+"""Helpers shared by the GPU parity tests: run the HIP path and the fp64 oracle on the same
+seeded inputs and measure the differences.  (Test code: may import both sides.)"""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+from paper_2502_12784_amd import synth
+
+# Tolerances (fp16 / bf16 inputs): max-abs on O and LSE, relative L2 on the gradients.
+#
+# O is compared as  |O - O_ref| <= TOL_ABS + half_ulp_out(O_ref) + operand_rounding, where
+#   * half_ulp_out is the unavoidable single rounding of the result to the 16-bit output
+#     type (up to |x| * 2^-8 for bf16, which alone exceeds 2e-3 once |x| >= 0.5);
+#   * operand_rounding is nonzero for bf16 only: the method runs O = P V on bf16 matrix
+#     cores, so P is rounded to 8 significant bits first.  That perturbs O_i by at most
+#     2^-9 * sum_j P_ij |V_jk| (the oracle evaluates this bound exactly as P |V|).  For fp16
+#     the same bound is 2^-12 * P|V| < 1e-3 for these inputs and stays inside TOL_ABS.
+# The raw max-abs error is always reported next to it.
+TOL_ABS = 2e-3
+TOL_REL_L2 = 1e-2
+
+
+def half_ulp(x64: np.ndarray, dtype: str) -> np.ndarray:
+    """Half a unit in the last place of the 16-bit output type at |x| (normal range)."""
+    mant = 10 if dtype == synth.F16 else 7
+    ax = np.abs(x64)
+    min_exp = -14 if dtype == synth.F16 else -126
+    e = np.floor(np.log2(np.maximum(ax, 2.0 ** min_exp)))
+    return 0.5 * 2.0 ** (e - mant)
+
+
+def to_device(bits: np.ndarray, dtype: str):
+    import torch
+    t = torch.from_numpy(bits.view(np.int16).copy()).cuda()
+    return t.view(torch.float16 if dtype == synth.F16 else torch.bfloat16)
+
+
+def to_f64(t) -> np.ndarray:
+    import torch
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def run_gpu(inp, dtype, scale, causal):
+    """Forward then backward through the C ABI on the forward's own O and LSE."""
+    import torch
+    from paper_2502_12784_amd import spark_mha_bwd, spark_mha_fwd
+    Q, K, V, dO = (to_device(inp[n], dtype) for n in ("Q", "K", "V", "dO"))
+    O, LSE = spark_mha_fwd(Q, K, V, scale, causal)
+    dQ, dK, dV = spark_mha_bwd(Q, K, V, O, LSE, dO, scale, causal)
+    torch.cuda.synchronize()
+    return {"O": O, "LSE": LSE, "dQ": dQ, "dK": dK, "dV": dV}
+
+
+def run_oracle(inp, dtype, scale, causal, heads=None):
+    """Oracle on all heads, or on the flat head indices `heads` of [B,H,N,d] bit arrays."""
+    arrs = {}
+    for n in ("Q", "K", "V", "dO"):
+        a = inp[n]
+        if heads is not None:
+            B, H, N, d = a.shape
+            a = a.reshape(B * H, 1, N, d)[list(heads)]
+        arrs[n] = synth.bits_to_f64(a, dtype)
+    # scale as the fp32 value the kernel receives
+    s = float(np.float32(scale))
+    ref = oracle.mha_bwd(arrs["Q"], arrs["K"], arrs["V"], arrs["dO"], s, causal)
+    if dtype == synth.BF16:  # bound on the effect of rounding P to bf16: 2^-9 * P |V|
+        ref["O_operand_rounding"] = 2.0 ** -9 * oracle.mha_fwd(arrs["Q"], arrs["K"], np.abs(arrs["V"]),
+                                                               s, causal)[0]
+    return ref
+
+
+def compare(gpu, ref, dtype, heads=None):
+    """Return error measures; `heads` selects flat heads of the GPU tensors to match `ref`."""
+    out = {}
+
+    def pick(t):
+        a = to_f64(t)
+        if heads is not None:
+            a = a.reshape((-1, 1) + a.shape[2:])[list(heads)]
+        return a
+
+    o_gpu, o_ref = pick(gpu["O"]), ref["O"]
+    err = np.abs(o_gpu - o_ref)
+    out["O_maxabs"] = float(err.max())
+    allow = half_ulp(o_ref, dtype) + ref.get("O_operand_rounding", 0.0)
+    out["O_excess"] = float((err - allow).max())  # must stay <= TOL_ABS
+    out["LSE_maxabs"] = float(np.abs(pick(gpu["LSE"]) - ref["LSE"]).max())
+    for n in ("dQ", "dK", "dV"):
+        g, r = pick(gpu[n]), ref[n]
+        rn = np.linalg.norm(r)
+        if rn < 1e-9 * np.sqrt(r.size):
+            # degenerate case with an exactly zero gradient (e.g. one key: dS = 0): compare the
+            # RMS error with a unit-scale gradient instead of dividing by zero
+            rn = np.sqrt(r.size)
+        out[n + "_relL2"] = float(np.linalg.norm(g - r) / rn)
+        out[n + "_finite"] = bool(np.isfinite(g).all())
+    return out
+
+
+def assert_within_tolerance(m, label=""):
+    assert m["O_excess"] <= TOL_ABS, (label, m)
+    assert m["LSE_maxabs"] <= TOL_ABS, (label, m)
+    for n in ("dQ", "dK", "dV"):
+        assert m[n + "_finite"], (label, m)
+        assert m[n + "_relL2"] <= TOL_REL_L2, (label, m)

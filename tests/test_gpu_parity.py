@@ -1,0 +1,90 @@
+"""GPU parity: HIP path (through the C ABI) against the fp64 CPU oracle, same seeded inputs.
+
+Bar: |O - O_ref| <= 2e-3 + half an output ulp at |O_ref| (the output is rounded once to
+fp16/bf16; 2e-3 bounds the computational error), |LSE - LSE_ref| <= 2e-3, and relative L2
+error <= 1e-2 for each of dQ, dK, dV.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from paper_2502_12784_amd import synth
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_full(B, H, N, d, dtype, causal, seed, sigma_qk=1.0, scale=None):
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    inp = synth.make_inputs(B, H, N, d, dtype, seed, sigma_qk=sigma_qk)
+    gpu = pu.run_gpu(inp, dtype, scale, causal)
+    ref = pu.run_oracle(inp, dtype, scale, causal)
+    m = pu.compare(gpu, ref, dtype)
+    print(f"\n[parity] B={B} H={H} N={N} d={d} {dtype} causal={causal}: {m}", flush=True)
+    return m
+
+
+# Small shapes, every head checked element by element: several tiles, ragged tails,
+# both head dims, both dtypes, both mask settings.
+SMALL = [
+    (1, 2, 128, 64), (2, 2, 256, 128), (1, 3, 320, 64), (1, 2, 384, 128),
+    (2, 1, 1, 64), (1, 2, 63, 128), (1, 2, 65, 64), (1, 1, 200, 128), (1, 2, 333, 64),
+    (1, 1, 777, 128),
+]
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+@pytest.mark.parametrize("shape", SMALL)
+def test_small_shapes_all_elements(shape, dtype, causal):
+    B, H, N, d = shape
+    m = _run_full(B, H, N, d, dtype, causal, seed=7000 + N + d)
+    pu.assert_within_tolerance(m, (shape, dtype, causal))
+
+
+def test_config_C1_full():
+    w = synth.WORKLOADS["C1"]
+    m = _run_full(w.B, w.H, w.N, w.d, w.dtype, w.causal, w.seed, w.sigma_qk)
+    pu.assert_within_tolerance(m, "C1")
+
+
+def test_wide_logits_small():
+    """Logits with std 3 (the long-sequence config's distribution) at a size checked in full."""
+    m = _run_full(1, 2, 512, 64, synth.F16, False, seed=4242, sigma_qk=math.sqrt(3.0))
+    pu.assert_within_tolerance(m, "wide logits")
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
+def test_full_size_configs_sampled_heads(name):
+    """Full-size run in the benchmark's launch configuration; the oracle checks the first,
+    a middle and the last (batch, head) element by element."""
+    w = synth.WORKLOADS[name]
+    inp = synth.make_workload_inputs(w)
+    gpu = pu.run_gpu(inp, w.dtype, w.scale, w.causal)
+    BH = w.B * w.H
+    heads = sorted({0, BH // 2 + 1, BH - 1}) if w.N <= 4096 else [0, BH - 1]
+    ref = pu.run_oracle(inp, w.dtype, w.scale, w.causal, heads=heads)
+    m = pu.compare(gpu, ref, w.dtype, heads=heads)
+    print(f"\n[parity] {name} heads={heads}: {m}", flush=True)
+    pu.assert_within_tolerance(m, name)
+    # properties that hold at any size, checked on every head of the GPU result
+    dK = pu.to_f64(gpu["dK"]); dV = pu.to_f64(gpu["dV"])
+    dO = synth.bits_to_f64(inp["dO"], w.dtype)
+    # columns of dK sum to zero over keys; sum_j dV_j = sum_i dO_i (rows of P sum to one)
+    scale_k = np.abs(dK).sum(2).max()
+    assert np.abs(dK.sum(2)).max() <= 2e-2 * scale_k
+    assert np.abs(dV.sum(2) - dO.sum(2)).max() <= 2e-2 * np.abs(dO).sum(2).max()
+    for n in ("O", "LSE", "dQ", "dK", "dV"):
+        assert np.isfinite(pu.to_f64(gpu[n])).all(), n
+
+
+def test_bitwise_reproducible():
+    """No atomics anywhere: two runs give identical bits."""
+    import torch
+    w = synth.WORKLOADS["C3"]
+    inp = synth.make_inputs(2, 2, w.N, w.d, w.dtype, 99)
+    a = pu.run_gpu(inp, w.dtype, w.scale, True)
+    b = pu.run_gpu(inp, w.dtype, w.scale, True)
+    for n in ("O", "LSE", "dQ", "dK", "dV"):
+        assert torch.equal(a[n], b[n]), n
