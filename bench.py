@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused MHA hot path on one MI355X.
+
+One step = spark_mha_fwd followed by spark_mha_bwd (D pre-pass, dK/dV kernel, dQ kernel) on
+one synthetic batch that is already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--all] [--no-cpu]
+
+`value` is counted TFLOP/s of fwd+bwd: forward 4*B*H*N^2*d flops (half if causal), backward
+2.5x that (five contractions), divided by the wall time of the timed steps.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = 2500.0  # MI355X dense fp16 = bf16 MFMA peak (vendor figure, no sparsity)
+
+
+def read_traffic(workload: str, kernel: str):
+    """HBM bytes per launch measured with rocprofv3 counters, if a summary is committed."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
+    try:
+        with open(path) as f:
+            for line in f:
+                m = re.match(r"\s*%s\s+traffic_bytes_per_launch\s*[:=]\s*([0-9.eE+]+)" % re.escape(kernel), line)
+                if m:
+                    return float(m.group(1))
+    except OSError:
+        pass
+    return None
+
+
+def time_workload(w, steps, warmup):
+    import torch
+    from paper_2502_12784_amd import HipEvents, spark_mha_bwd, spark_mha_fwd, synth
+    from paper_2502_12784_amd.binding import _dtype_code, spark_mha_bwd_workspace_bytes
+
+    def dev(bits):
+        t = torch.from_numpy(bits.view(np.int16)).cuda()
+        return t.view(torch.float16 if w.dtype == synth.F16 else torch.bfloat16)
+
+    inp = synth.make_workload_inputs(w)
+    Q, K, V, dO = (dev(inp[n]) for n in ("Q", "K", "V", "dO"))
+    del inp
+    O = torch.empty_like(Q)
+    LSE = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device="cuda")
+    dQ, dK, dV = (torch.empty_like(Q) for _ in range(3))
+    ws = torch.empty(max(16, spark_mha_bwd_workspace_bytes(w.B, w.H, w.N, w.d, _dtype_code(Q))),
+                     dtype=torch.uint8, device="cuda")
+
+    def step(ev=None, base=0):
+        if ev is not None:
+            ev.record(base)
+        spark_mha_fwd(Q, K, V, w.scale, w.causal, O=O, LSE=LSE)
+        spark_mha_bwd(Q, K, V, O, LSE, dO, w.scale, w.causal, dQ=dQ, dK=dK, dV=dV, workspace=ws,
+                      events=None if ev is None else (ev, base + 1))
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    # per step: event 0 before fwd, 1..4 recorded by spark_mha_bwd_marked
+    ev = HipEvents(5 * steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        step(ev, 5 * s)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    k = {"fwd": 0.0, "bwd_dot": 0.0, "bwd_dkdv": 0.0, "bwd_dq": 0.0}
+    for s in range(steps):
+        b = 5 * s
+        k["fwd"] += ev.elapsed_ms(b, b + 1)
+        k["bwd_dot"] += ev.elapsed_ms(b + 1, b + 2)
+        k["bwd_dkdv"] += ev.elapsed_ms(b + 2, b + 3)
+        k["bwd_dq"] += ev.elapsed_ms(b + 3, b + 4)
+    ev.close()
+    k = {n: v / steps for n, v in k.items()}
+    return wall / steps * 1e3, k
+
+
+def cpu_baseline(w, budget_s=12.0):
+    """Time the fp64 oracle (as it stands) on a bounded sample of heads of the same workload."""
+    import oracle
+    from paper_2502_12784_amd import synth
+    BH = w.B * w.H
+    order = [0, BH - 1] + list(range(1, BH - 1))
+    done, t_total = 0, 0.0
+    heads_done = []
+    s = float(np.float32(w.scale))
+    chunk = 1
+    while done < BH and t_total < budget_s:
+        heads = order[done:done + chunk]
+        inp = synth.make_workload_inputs(w, heads=heads)
+        a = {n: synth.bits_to_f64(inp[n], w.dtype) for n in ("Q", "K", "V", "dO")}
+        t0 = time.perf_counter()
+        oracle.mha_fwd(a["Q"], a["K"], a["V"], s, w.causal)
+        oracle.mha_bwd(a["Q"], a["K"], a["V"], a["dO"], s, w.causal)
+        t_total += time.perf_counter() - t0
+        done += len(heads)
+        heads_done += heads
+    flops = (w.fwd_flops + w.bwd_flops) * done / BH
+    return {
+        "value": flops / t_total / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": "%d of %d (batch, head) slices of %s, fwd then bwd in fp64, %.1f s" % (done, BH, w.name, t_total),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C4", help="C1..C5 (default C4: N=4096, d=128, bf16, causal)")
+    ap.add_argument("--all", action="store_true", help="also time the other four configs (extra field)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (heads shard with no communication); "
+                 "--gpus %d is not supported, use --gpus 1" % args.gpus)
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    from paper_2502_12784_amd import load_library, synth
+    load_library()  # fail loudly if the HIP library is missing
+
+    w = synth.WORKLOADS[args.workload]
+    ms, k = time_workload(w, args.steps, args.warmup)
+    flops_step = w.fwd_flops + w.bwd_flops
+    value = flops_step / (ms * 1e-3) / 1e12
+
+    # algorithmic flops per launch: forward 2 contractions; dK/dV kernel 4 (S, dP, dV, dK);
+    # dQ kernel 1 (its recomputed S and dP are not counted twice) -> backward total 5.
+    gemm = w.fwd_flops / 2.0
+    alg = {"fwd": 2 * gemm, "bwd_dkdv": 4 * gemm, "bwd_dq": 1 * gemm}
+    dom = max(alg, key=lambda n: k[n])
+    achieved = alg[dom] / (k[dom] * 1e-3) / 1e12
+    out = {
+        "metric": "MHA fwd+bwd TFLOP/s (counted flops: fwd 4*B*H*N^2*d, half if causal; bwd 2.5x)",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": "%s: B=%d H=%d N=%d d=%d %s %s scale=1/sqrt(d), Q,K~N(0,%.3g) V,dO~N(0,1), seed %d"
+                   % (w.name, w.B, w.H, w.N, w.d, w.dtype, "causal" if w.causal else "non-causal",
+                      w.sigma_qk ** 2, w.seed)},
+        "pct_of_mfma_peak": 100.0 * value / PEAK_TFLOPS,
+        "fwd_tflops": w.fwd_flops / (k["fwd"] * 1e-3) / 1e12,
+        "bwd_tflops": w.bwd_flops / ((k["bwd_dot"] + k["bwd_dkdv"] + k["bwd_dq"]) * 1e-3) / 1e12,
+        "kernel_ms": k,
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_TFLOPS,
+                     "traffic": read_traffic(w.name, dom)},
+    }
+    if args.all:
+        others = {}
+        for name, ww in synth.WORKLOADS.items():
+            if name == w.name:
+                continue
+            m2, k2 = time_workload(ww, max(5, args.steps // 2), args.warmup)
+            others[name] = {"ms_per_step": m2, "tflops": (ww.fwd_flops + ww.bwd_flops) / (m2 * 1e-3) / 1e12,
+                            "fwd_tflops": ww.fwd_flops / (k2["fwd"] * 1e-3) / 1e12,
+                            "bwd_tflops": ww.bwd_flops / ((k2["bwd_dot"] + k2["bwd_dkdv"] + k2["bwd_dq"]) * 1e-3) / 1e12,
+                            "kernel_ms": k2}
+        out["other_configs"] = others
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

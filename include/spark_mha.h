@@ -20,8 +20,9 @@
  *     element type `dtype` (IEEE fp16 or bfloat16).  LSE has shape [B, H, N],
  *     fp32.  Pointers must be 16-byte aligned.  Inputs and outputs must not
  *     alias each other.
- *   - Supported: d in {64, 128}; any N >= 1; B, H >= 1 with B*H <= 65535*... (see
- *     SPARK_ERR_SHAPE); scale finite and > 0; causal in {0, 1}.
+ *   - Supported: d in {64, 128}; any N >= 1; B, H >= 1; scale finite and > 0; causal is
+ *     a flag (0 = all keys, nonzero = masked).  Size limits: B*H*ceil(N/64) < 2^31 and
+ *     N*d < 2^31.  Anything else returns SPARK_ERR_SHAPE; nothing is silently mis-computed.
  *   - causal != 0: query i attends to keys j <= i (Sec. 2.1, masked MHA).
  *   - Arithmetic: both contractions run on fp16/bf16 MFMA with fp32
  *     accumulation; the softmax statistics, P before packing, the O
@@ -48,8 +49,8 @@ typedef enum { SPARK_F16 = 0, SPARK_BF16 = 1 } spark_dtype_t;
 typedef enum {
   SPARK_OK = 0,
   SPARK_ERR_NULL = -1,      /* a required pointer is NULL */
-  SPARK_ERR_SHAPE = -2,     /* B, H or N < 1; d not 64/128; B*H*N*d overflows 2^31 elements per
-                               head-batch slice limits (see below); scale not finite or <= 0 */
+  SPARK_ERR_SHAPE = -2,     /* B, H or N < 1; d not 64/128; a size limit exceeded; scale not
+                               finite or <= 0 */
   SPARK_ERR_DTYPE = -3,     /* dtype is neither SPARK_F16 nor SPARK_BF16 */
   SPARK_ERR_ALIGN = -4,     /* a pointer is not 16-byte aligned */
   SPARK_ERR_WORKSPACE = -5, /* workspace too small (see spark_mha_bwd_workspace_bytes) */
@@ -64,7 +65,6 @@ typedef enum {
  *             keys of the scaled logits, LSE_i = ln sum_j exp(scale * q_i . k_j).
  *             (This is the row statistic the paper's Sec. 3.3 calls "LES" and
  *             uses as Exp(S_ij - L_i).)
- * Limits: B*H*ceil(N/128) < 2^31 and N*d < 2^31.
  * Returns SPARK_OK or a negative spark_status_t.
  */
 int spark_mha_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
@@ -94,6 +94,18 @@ int spark_mha_bwd(const void* Q, const void* K, const void* V, const void* O, co
                   void* workspace, size_t workspace_bytes,
                   int B, int H, int N, int d, float scale, int causal,
                   spark_dtype_t dtype, void* stream);
+
+/*
+ * spark_mha_bwd with profiling marks: identical work, and additionally records the caller's
+ * four HIP events (hipEvent_t handles, host array) on `stream`: events[0] before the D
+ * pre-pass, events[1] after it, events[2] after the dK/dV kernel, events[3] after the dQ
+ * kernel.  The caller creates, reads and destroys the events.  SPARK_ERR_NULL if any is NULL.
+ */
+int spark_mha_bwd_marked(const void* Q, const void* K, const void* V, const void* O,
+                         const float* LSE, const void* dO, void* dQ, void* dK, void* dV,
+                         void* workspace, size_t workspace_bytes,
+                         int B, int H, int N, int d, float scale, int causal,
+                         spark_dtype_t dtype, void* stream, void* const events[4]);
 
 /* Static, NUL-terminated description of a status code. */
 const char* spark_status_str(int status);

@@ -4,6 +4,8 @@
 ``synth`` generates the seeded synthetic workloads; ``build`` compiles the library.
 """
 from .binding import (  # noqa: F401
+    EXPORTS,
+    HipEvents,
     SparkError,
     load_library,
     spark_mha_bwd,

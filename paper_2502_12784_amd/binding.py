@@ -16,7 +16,8 @@ LIB_PATH = os.path.join(HERE, "libspark_mha.so")
 SPARK_F16 = 0
 SPARK_BF16 = 1
 
-EXPORTS = ("spark_mha_fwd", "spark_mha_bwd", "spark_mha_bwd_workspace_bytes", "spark_status_str")
+EXPORTS = ("spark_mha_fwd", "spark_mha_bwd", "spark_mha_bwd_marked",
+           "spark_mha_bwd_workspace_bytes", "spark_status_str")
 
 _lib = None
 
@@ -43,6 +44,8 @@ def load_library() -> ctypes.CDLL:
     lib.spark_mha_bwd_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.spark_mha_bwd.restype = i
     lib.spark_mha_bwd.argtypes = [vp] * 10 + [ctypes.c_size_t, i, i, i, i, f, i, i, vp]
+    lib.spark_mha_bwd_marked.restype = i
+    lib.spark_mha_bwd_marked.argtypes = lib.spark_mha_bwd.argtypes + [ctypes.POINTER(vp)]
     lib.spark_status_str.restype = ctypes.c_char_p
     lib.spark_status_str.argtypes = [i]
     _lib = lib
@@ -101,9 +104,57 @@ def spark_mha_bwd_workspace_bytes(B: int, H: int, N: int, d: int, dtype_code: in
     return int(load_library().spark_mha_bwd_workspace_bytes(B, H, N, d, dtype_code))
 
 
+class HipEvents:
+    """A fixed set of HIP events created through the HIP runtime itself (for
+    spark_mha_bwd_marked and for timing on the stream the kernels run on)."""
+
+    def __init__(self, n: int):
+        self._hip = ctypes.CDLL("libamdhip64.so")
+        self._hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self._hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        self._hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self._hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p,
+                                                  ctypes.c_void_p]
+        self._hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.handles = (ctypes.c_void_p * n)()
+        for k in range(n):
+            ev = ctypes.c_void_p()
+            if self._hip.hipEventCreate(ctypes.byref(ev)) != 0:
+                raise RuntimeError("hipEventCreate failed")
+            self.handles[k] = ev
+
+    def record(self, k: int) -> None:
+        if self._hip.hipEventRecord(self.handles[k], _stream_ptr()) != 0:
+            raise RuntimeError("hipEventRecord failed")
+
+    def synchronize(self, k: int) -> None:
+        if self._hip.hipEventSynchronize(self.handles[k]) != 0:
+            raise RuntimeError("hipEventSynchronize failed")
+
+    def elapsed_ms(self, a: int, b: int) -> float:
+        ms = ctypes.c_float()
+        if self._hip.hipEventElapsedTime(ctypes.byref(ms), self.handles[a], self.handles[b]) != 0:
+            raise RuntimeError("hipEventElapsedTime failed")
+        return float(ms.value)
+
+    def slice_ptr(self, first: int):
+        """Pointer to handles[first:], as the `events` argument of spark_mha_bwd_marked."""
+        return ctypes.cast(ctypes.byref(self.handles, first * ctypes.sizeof(ctypes.c_void_p)),
+                           ctypes.POINTER(ctypes.c_void_p))
+
+    def close(self) -> None:
+        for h in self.handles:
+            if h:
+                self._hip.hipEventDestroy(h)
+        self.handles = (ctypes.c_void_p * 0)()
+
+
 def spark_mha_bwd(Q, K, V, O, LSE, dO, scale: float, causal: bool, dQ=None, dK=None, dV=None,
-                  workspace=None):
-    """dQ, dK, dV = fused attention backward on the current stream."""
+                  workspace=None, events=None):
+    """dQ, dK, dV = fused attention backward on the current stream.
+
+    ``events``: optional ``(HipEvents, first_index)``; then spark_mha_bwd_marked is called and
+    records 4 events starting at that index around the three kernels."""
     import torch
     lib = load_library()
     B, H, N, d = Q.shape
@@ -120,8 +171,12 @@ def spark_mha_bwd(Q, K, V, O, LSE, dO, scale: float, causal: bool, dQ=None, dK=N
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
     wbytes = workspace.numel() * workspace.element_size()
-    _check(lib.spark_mha_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(),
-                             dO.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
-                             workspace.data_ptr(), wbytes, B, H, N, d, float(scale),
-                             int(bool(causal)), code, _stream_ptr()))
+    args = [Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(),
+            dO.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
+            workspace.data_ptr(), wbytes, B, H, N, d, float(scale),
+            int(bool(causal)), code, _stream_ptr()]
+    if events is None:
+        _check(lib.spark_mha_bwd(*args))
+    else:
+        _check(lib.spark_mha_bwd_marked(*args, events[0].slice_ptr(events[1])))
     return dQ, dK, dV

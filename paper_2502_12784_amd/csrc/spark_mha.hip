@@ -52,20 +52,25 @@ int launch_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
 template <typename T, int D, bool CAUSAL>
 int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
                const void* dO, void* dQ, void* dK, void* dV, float* Dws, int BH, int N,
-               float scale, hipStream_t st) {
+               float scale, hipStream_t st, void* const* ev) {
   const T* q = static_cast<const T*>(Q);
   const T* k = static_cast<const T*>(K);
   const T* v = static_cast<const T*>(V);
   const T* o = static_cast<const T*>(O);
   const T* dout = static_cast<const T*>(dO);
   const float scale_log2 = scale * 1.4426950408889634f;
+  // optional profiling marks between the kernels (spark_mha_bwd_marked)
+  auto mark = [&](int i) {
+    return !ev || hipEventRecord(static_cast<hipEvent_t>(ev[i]), st) == hipSuccess;
+  };
 
+  if (!mark(0)) return SPARK_ERR_LAUNCH;
   {  // D = rowsum(dO o O): one wave per 64/(D/8) rows
     constexpr int ROWS_PER_BLOCK = 256 / (D / 8);
     const int64_t rows = (int64_t)BH * N;
     const unsigned grid = (unsigned)((rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK);
     hipLaunchKernelGGL((mha_bwd_dot_kernel<T, D>), dim3(grid), dim3(256), 0, st, o, dout, Dws, rows);
-    if (hipGetLastError() != hipSuccess) return SPARK_ERR_LAUNCH;
+    if (hipGetLastError() != hipSuccess || !mark(1)) return SPARK_ERR_LAUNCH;
   }
   {  // dK, dV: one workgroup per tile of 128 keys
     using C = BwdKvCfg<D>;
@@ -76,7 +81,7 @@ int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const
     hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * nkt)), dim3(256), C::SMEM, st, q, k, v, dout,
                        LSE, Dws, static_cast<T*>(dK), static_cast<T*>(dV), N, nkt, scale,
                        scale_log2);
-    if (hipGetLastError() != hipSuccess) return SPARK_ERR_LAUNCH;
+    if (hipGetLastError() != hipSuccess || !mark(2)) return SPARK_ERR_LAUNCH;
   }
   {  // dQ: one workgroup per tile of 128 queries
     using C = BwdQCfg<D>;
@@ -86,7 +91,7 @@ int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const
     const int nqt = (N + C::BM - 1) / C::BM;
     hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * nqt)), dim3(256), C::SMEM, st, q, k, v, dout,
                        LSE, Dws, static_cast<T*>(dQ), N, nqt, scale, scale_log2);
-    if (hipGetLastError() != hipSuccess) return SPARK_ERR_LAUNCH;
+    if (hipGetLastError() != hipSuccess || !mark(3)) return SPARK_ERR_LAUNCH;
   }
   return SPARK_OK;
 }
@@ -128,10 +133,10 @@ size_t spark_mha_bwd_workspace_bytes(int B, int H, int N, int d, spark_dtype_t d
   return (size_t)B * H * N * sizeof(float);
 }
 
-int spark_mha_bwd(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
-                  const void* dO, void* dQ, void* dK, void* dV, void* workspace,
-                  size_t workspace_bytes, int B, int H, int N, int d, float scale, int causal,
-                  spark_dtype_t dtype_e, void* stream) {
+static int bwd_impl(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
+                    const void* dO, void* dQ, void* dK, void* dV, void* workspace,
+                    size_t workspace_bytes, int B, int H, int N, int d, float scale, int causal,
+                    spark_dtype_t dtype_e, void* stream, void* const* ev) {
   const int dtype = (int)dtype_e;
   if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV || !workspace) return SPARK_ERR_NULL;
   const int rc = check_common(B, H, N, d, scale, dtype);
@@ -144,7 +149,25 @@ int spark_mha_bwd(const void* Q, const void* K, const void* V, const void* O, co
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int BH = B * H;
   float* Dws = static_cast<float*>(workspace);
-  SPARK_DISPATCH(launch_bwd, Q, K, V, O, LSE, dO, dQ, dK, dV, Dws, BH, N, scale, st);
+  SPARK_DISPATCH(launch_bwd, Q, K, V, O, LSE, dO, dQ, dK, dV, Dws, BH, N, scale, st, ev);
+}
+
+int spark_mha_bwd(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
+                  const void* dO, void* dQ, void* dK, void* dV, void* workspace,
+                  size_t workspace_bytes, int B, int H, int N, int d, float scale, int causal,
+                  spark_dtype_t dtype, void* stream) {
+  return bwd_impl(Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, B, H, N, d, scale,
+                  causal, dtype, stream, nullptr);
+}
+
+int spark_mha_bwd_marked(const void* Q, const void* K, const void* V, const void* O,
+                         const float* LSE, const void* dO, void* dQ, void* dK, void* dV,
+                         void* workspace, size_t workspace_bytes, int B, int H, int N, int d,
+                         float scale, int causal, spark_dtype_t dtype, void* stream,
+                         void* const events[4]) {
+  if (!events || !events[0] || !events[1] || !events[2] || !events[3]) return SPARK_ERR_NULL;
+  return bwd_impl(Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, B, H, N, d, scale,
+                  causal, dtype, stream, events);
 }
 
 const char* spark_status_str(int status) {
