@@ -124,6 +124,9 @@ def main():
     ap.add_argument("--workload", default="C4", help="C1..C5 (default C4: N=4096, d=128, bf16, causal)")
     ap.add_argument("--all", action="store_true", help="also time the other four configs (extra field)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run 5 plain device copies of 256 MiB (reads 256 MiB, writes 256 MiB each) "
+                         "so FETCH_SIZE / WRITE_SIZE counters can be scaled against a known size")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (heads shard with no communication); "
@@ -134,6 +137,14 @@ def main():
         sys.exit("bench.py: no GPU visible")
     from paper_2502_12784_amd import load_library, synth
     load_library()  # fail loudly if the HIP library is missing
+
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     w = synth.WORKLOADS[args.workload]
     ms, k = time_workload(w, args.steps, args.warmup)

@@ -1,0 +1,110 @@
+"""C-ABI checks that need no GPU: the library loads, exports every symbol the header declares,
+and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2502_12784_amd as pkg
+from paper_2502_12784_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "spark_mha.h")
+
+OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_WS, E_LAUNCH = 0, -1, -2, -3, -4, -5, -6
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return pkg.load_library()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spark_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(pkg.EXPORTS), (names, pkg.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings(lib):
+    seen = set()
+    for code in (OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_WS, E_LAUNCH, -99):
+        s = pkg.status_str(code)
+        assert isinstance(s, str) and s
+        seen.add(s)
+    assert len(seen) == 8
+
+
+def _fwd(lib, q=0x1000, k=0x2000, v=0x3000, o=0x4000, lse=0x5000, B=1, H=1, N=128, d=64,
+         scale=0.125, causal=0, dtype=0):
+    return lib.spark_mha_fwd(q, k, v, o, lse, B, H, N, d, scale, causal, dtype, None)
+
+
+def test_fwd_validation_has_no_side_effects(lib):
+    # fake (never dereferenced) pointers: every call below must fail before any launch
+    assert _fwd(lib, q=None) == E_NULL
+    assert _fwd(lib, lse=None) == E_NULL
+    assert _fwd(lib, B=0) == E_SHAPE
+    assert _fwd(lib, N=0) == E_SHAPE
+    assert _fwd(lib, d=96) == E_SHAPE
+    assert _fwd(lib, d=32) == E_SHAPE
+    assert _fwd(lib, scale=0.0) == E_SHAPE
+    assert _fwd(lib, scale=-1.0) == E_SHAPE
+    assert _fwd(lib, scale=float("nan")) == E_SHAPE
+    assert _fwd(lib, scale=float("inf")) == E_SHAPE
+    assert _fwd(lib, dtype=2) == E_DTYPE
+    assert _fwd(lib, k=0x2008) == E_ALIGN
+    assert _fwd(lib, B=1 << 20, H=1 << 10, N=1 << 12) == E_SHAPE  # grid would overflow
+    assert _fwd(lib, N=1 << 25, d=128) == E_SHAPE                 # N*d >= 2^31
+
+
+def _bwd(lib, fn="spark_mha_bwd", ws=0xA000, ws_bytes=1 << 20, dq=0x7000, B=1, H=1, N=128, d=64,
+         scale=0.125, dtype=0, extra=()):
+    f = getattr(lib, fn)
+    return f(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, dq, 0x8000, 0x9000, ws, ws_bytes,
+             B, H, N, d, scale, 0, dtype, None, *extra)
+
+
+def test_bwd_validation(lib):
+    assert _bwd(lib, dq=None) == E_NULL
+    assert _bwd(lib, ws=None) == E_NULL
+    assert _bwd(lib, d=100) == E_SHAPE
+    assert _bwd(lib, dtype=7) == E_DTYPE
+    assert _bwd(lib, dq=0x7004) == E_ALIGN
+    need = pkg.spark_mha_bwd_workspace_bytes(1, 1, 128, 64, 0)
+    assert need == 128 * 4
+    assert _bwd(lib, ws_bytes=need - 1) == E_WS
+    assert _bwd(lib, fn="spark_mha_bwd_marked", extra=(None,)) == E_NULL
+    evs = (ctypes.c_void_p * 4)(1, 2, None, 4)
+    assert _bwd(lib, fn="spark_mha_bwd_marked", extra=(evs,)) == E_NULL
+
+
+def test_workspace_bytes(lib):
+    assert pkg.spark_mha_bwd_workspace_bytes(4, 16, 4096, 128, 1) == 4 * 16 * 4096 * 4
+    assert pkg.spark_mha_bwd_workspace_bytes(4, 16, 4096, 100, 1) == 0
+    assert pkg.spark_mha_bwd_workspace_bytes(0, 16, 4096, 128, 1) == 0
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    x = torch.zeros(1, 1, 8, 64, dtype=torch.float16)
+    with pytest.raises(ValueError):
+        pkg.spark_mha_fwd(x, x, x, 0.125, False)
+
+
+def test_product_does_not_import_oracle():
+    """The product package must not reach into oracle/ (parity would be void)."""
+    pkgdir = os.path.join(ROOT, "paper_2502_12784_amd")
+    for dirpath, _, files in os.walk(pkgdir):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle|#include\s*[<\"].*oracle", text, flags=re.M), f
+                assert "liboracle" not in text and "mha_oracle" not in text, f
