@@ -108,20 +108,83 @@ static __device__ __forceinline__ void store_transposed(const f32x16 (&acc)[D / 
   }
 }
 
-// A-operand (32 rows of the TRANSPOSE of a row-major LDS tile, 16 k-slots) for d-tile `dt`:
-// k-slot (g, j) is tile row  rbase + 8*(j/4) + 4g + (j%4)  (the order of packed C registers).
-template <typename T, int STRIDE>
-static __device__ __forceinline__ typename Frag<T>::v8 read_transposed(SPARK_LDS const char* tile,
-                                                                      int rbase, int dt, int lane) {
+// ---------------------------------------------------------------------------------------
+// Swizzled LDS tiles.  A tile that is read both row-wise (16 bytes of one row per lane: A/B
+// operands contracted over d) and transposed (ds_read_b64_tr_b16 over 4 rows x 64 bytes)
+// cannot be made conflict-free by padding alone, so rows are unpadded (2*D bytes) and the
+// 16-byte chunk index is XORed with a function of the row:
+//   D = 128 (16 chunks/row):  f(r) = ((r & 3) << 2) | ((r >> 2) & 3)
+//   D =  64 ( 8 chunks/row):  x = (r >> 1) & 7,  f = ((x & 1) << 2) | ((x >> 1) & 3)
+// 16 consecutive rows at one logical chunk then fall into 16 different 16-byte bank groups,
+// and the 4 rows x 4 chunks of a transposing read into 16 different ones as well.  f depends
+// on r mod 16 only, so per-lane offsets are computed once and every tile / sub-tile / k-step
+// displacement is an immediate.
+// ---------------------------------------------------------------------------------------
+template <int D>
+static __device__ __forceinline__ int swz(int row) {
+  if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+  const int x = (row >> 1) & 7;
+  return ((x & 1) << 2) | ((x >> 1) & 3);
+}
+template <int D>
+static __device__ __forceinline__ int swz_off(int row, int chunk) {
+  return row * (2 * D) + ((chunk ^ swz<D>(row)) << 4);
+}
+
+// registers -> swizzled tile (thread t owns chunk t of every group of 256 chunks)
+template <int D, int ROWS>
+static __device__ __forceinline__ void tile_r2s_swz(SPARK_LDS char* dst, int tid,
+                                                    const u32x4 (&reg)[ROWS * (D / 8) / 256]) {
+  constexpr int CPR = D / 8;
+#pragma unroll
+  for (int i = 0; i < ROWS * CPR / 256; ++i) {
+    const int c = tid + 256 * i;
+    lds_write(dst, swz_off<D>(c / CPR, c % CPR), reg[i]);
+  }
+}
+
+// global (buffer view) -> registers, rows r0.. of a [N][D] matrix; rows past N read as zero
+template <int D, int ROWS>
+static __device__ __forceinline__ void tile_b2r(const BufView& view, int r0, int tid,
+                                                u32x4 (&reg)[ROWS * (D / 8) / 256]) {
+#pragma unroll
+  for (int i = 0; i < ROWS * (D / 8) / 256; ++i)
+    reg[i] = view.load16(tid * 16 + i * 4096, (uint32_t)r0 * (D * 2));
+}
+
+// Per-lane byte offsets into a swizzled tile.
+//   row[ks]   : 16-byte row read, row c32, logical chunk 2*ks + g      (A/B operand over d)
+//   tr[h][dt] : transposing read for d-tile dt, rows 8h + 4g + i16/4   (operand over rows)
+// Add (multiple of 16 rows) * 2*D bytes for other sub-tiles; the swizzle is unchanged by that.
+template <int D> struct SwzLane {
+  int row[D / 16];
+  int tr[2][D / 32];
+  // `bias` is added to every offset (a region in front of the tiles), so that all later
+  // displacements stay small enough for the 16-bit immediate of the DS instructions.
+  __device__ __forceinline__ explicit SwzLane(int lane, int bias = 0) {
+    const int g = lane >> 5, c32 = lane & 31, i16 = lane & 15;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) row[ks] = bias + swz_off<D>(c32, 2 * ks + g);
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+        tr[h][dt] = bias + swz_off<D>(8 * h + 4 * g + (i16 >> 2), dt * 4 + ((c32 >> 4) << 1) + ((i16 & 3) >> 1)) +
+                    (i16 & 1) * 8;
+  }
+};
+
+template <typename T>
+static __device__ __forceinline__ typename Frag<T>::v8 read_tr_pair(SPARK_LDS const char* tile, int off_lo,
+                                                                   int off_hi) {
   using v8 = typename Frag<T>::v8;
   using v4 = typename Frag<T>::v4;
-  const int g = lane >> 5, c32 = lane & 31, i16 = lane & 15;
-  const int row0 = rbase + 4 * g + (i16 >> 2);
-  const int col = dt * 32 + (c32 & 16) + 4 * (i16 & 3);
-  const v4 lo = lds_read_tr8<v4>(tile, row0 * STRIDE + col * 2);
-  const v4 hi = lds_read_tr8<v4>(tile, (row0 + 8) * STRIDE + col * 2);
+  const v4 lo = lds_read_tr8<v4>(tile, off_lo);
+  const v4 hi = lds_read_tr8<v4>(tile, off_hi);
   return join4<v8, v4>(lo, hi);
 }
+
+template <int V> struct IntC { static constexpr int value = V; };
 
 // ---------------------------------------------------------------------------------------
 // dK, dV
@@ -129,13 +192,14 @@ static __device__ __forceinline__ typename Frag<T>::v8 read_transposed(SPARK_LDS
 template <int D> struct BwdKvCfg {
   static constexpr int BN = 128;  // keys per workgroup (32 per wave)
   static constexpr int BM = 64;   // query rows per LDS stage (two 32-row steps)
-  static constexpr int STR = D * 2 + 16;
-  static constexpr int TILE = BM * STR;  // one of Q, dO
+  static constexpr int ROWB = D * 2;       // bytes per (swizzled, unpadded) row
+  static constexpr int TILE = BM * ROWB;   // one of Q, dO
   static constexpr int STAT = 2 * BM * 4;  // LSE*log2(e) and D of the stage's rows
-  static constexpr int STAGE = 2 * TILE + STAT;
+  static constexpr int STAGE = 2 * TILE;   // tiles only; LDS = [stat 0 | stat 1 | stage 0 | stage 1]
   static constexpr int OSTR = D * 2 + 16;
-  static constexpr int SMEM = 2 * STAGE;
+  static constexpr int SMEM = 2 * STAT + 2 * STAGE;
   static_assert(4 * 32 * OSTR <= SMEM, "epilogue staging must fit");
+  static_assert(2 * STAGE <= 65536, "tile displacements must fit the 16-bit offset field");
 };
 
 template <typename T, int D, bool CAUSAL>
@@ -160,10 +224,9 @@ __global__ __launch_bounds__(256) void mha_bwd_dkdv_kernel(
   const int kt = logical - head * nkt;  // causal: low key tiles (most queries) come first
 
   const size_t head_off = (size_t)head * N * D;
-  const T* Qh = Q + head_off;
-  const T* dOh = dO + head_off;
   const float* LSEh = LSE + (size_t)head * N;
   const float* Dh = Dws + (size_t)head * N;
+  const BufView qview(Q + head_off, (uint32_t)N * D * 2), doview(dO + head_off, (uint32_t)N * D * 2);
 
   const int k0w = kt * C::BN + wave * 32;  // first key of this wave
   const int krow = k0w + c32;
@@ -182,14 +245,16 @@ __global__ __launch_bounds__(256) void mha_bwd_dkdv_kernel(
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dk[dt][r] = 0.f; dv[dt][r] = 0.f; }
 
-  const int ns = (N + C::BM - 1) / C::BM;              // query stages in the sequence
-  const int s_begin = CAUSAL ? (kt * C::BN) / C::BM : 0;  // queries before the tile's first key see none of it
+  const int ns = (N + C::BM - 1) / C::BM;                 // query stages in the sequence
+  const int s_begin = CAUSAL ? (kt * C::BN) / C::BM : 0;  // earlier queries see none of this tile
+
+  const SwzLane<D> off(lane, 2 * C::STAT);  // offsets relative to smem, tiles start after the stats
 
   u32x4 qreg[NLD], doreg[NLD];
   float statreg = 0.f;
   auto load_stage = [&](int m) {
-    tile_g2r<D, C::BM>(Qh, m * C::BM, N, tid, qreg);
-    tile_g2r<D, C::BM>(dOh, m * C::BM, N, tid, doreg);
+    tile_b2r<D, C::BM>(qview, m * C::BM, tid, qreg);
+    tile_b2r<D, C::BM>(doview, m * C::BM, tid, doreg);
     if (tid < 2 * C::BM) {
       const int row = m * C::BM + (tid & (C::BM - 1));
       if (tid < C::BM)  // rows past the end get LSE = +inf so that P = 0 there
@@ -199,77 +264,122 @@ __global__ __launch_bounds__(256) void mha_bwd_dkdv_kernel(
     }
   };
   auto store_stage = [&](int buf) {
-    SPARK_LDS char* sb = smem + buf * C::STAGE;
-    tile_r2s<D, C::BM, C::STR>(sb, tid, qreg);
-    tile_r2s<D, C::BM, C::STR>(sb + C::TILE, tid, doreg);
-    if (tid < 2 * C::BM) lds_write(sb + 2 * C::TILE, tid * 4, statreg);
+    SPARK_LDS char* sb = smem + 2 * C::STAT + buf * C::STAGE;
+    tile_r2s_swz<D, C::BM>(sb, tid, qreg);
+    tile_r2s_swz<D, C::BM>(sb + C::TILE, tid, doreg);
+    if (tid < 2 * C::BM) lds_write(smem + buf * C::STAT, tid * 4, statreg);
   };
 
-  if (s_begin < ns) {
-    load_stage(s_begin);
-    store_stage(0);
-  }
+  load_stage(s_begin);
+  wait_vmem_all();  // K/V fragments and the first stage are in registers before the loop
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(kf[ks]), "+v"(vf[ks]));
+  store_stage(0);
   __syncthreads();
 
-  for (int m = s_begin; m < ns; ++m) {
-    const int buf = (m - s_begin) & 1;
+  // One LDS stage (64 queries) in buffer BUF; the next stage's global loads are in flight
+  // meanwhile and are written to the other buffer at the end.
+  auto stage = [&](auto bufc, int m) {
+    constexpr int BUF = decltype(bufc)::value;
     if (m + 1 < ns) load_stage(m + 1);
 
-    SPARK_LDS const char* qb = smem + buf * C::STAGE;
+    SPARK_LDS const char* qb = smem + BUF * C::STAGE;  // + off.* (which include the stats bias)
     SPARK_LDS const char* dob = qb + C::TILE;
-    SPARK_LDS const char* stb = dob + C::TILE;
+    SPARK_LDS const char* stb = smem + BUF * C::STAT;
 
 #pragma unroll
     for (int sub = 0; sub < C::BM / 32; ++sub) {
       const int q0s = m * C::BM + sub * 32;
       if (CAUSAL && q0s + 31 < k0w) continue;  // every query here precedes every key of the wave
       if (q0s >= N) continue;
+      constexpr int NG = KS / 2;
+      const int suboff = sub * 32 * C::ROWB;
 
+      // S = Q K^T and dP = dO V^T (lane = key column, registers = query rows); the Q / dO row
+      // fragments are read two k-steps ahead of the MFMAs that consume them.
       f32x16 s, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+      v8 fa[2][4];
+      auto load_agroup = [&](int gi) {
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const int off = (sub * 32 + c32) * C::STR + ks * 32 + g * 16;
-        const v8 qa = lds_read16<v8>(qb, off);
-        s = F::mfma(qa, kf[ks], s);
-        const v8 da = lds_read16<v8>(dob, off);
-        dp = F::mfma(da, vf[ks], dp);
+        for (int e = 0; e < 2; ++e) {
+          fa[gi & 1][2 * e] = lds_read16<v8>(qb, off.row[2 * gi + e] + suboff);
+          fa[gi & 1][2 * e + 1] = lds_read16<v8>(dob, off.row[2 * gi + e] + suboff);
+        }
+      };
+      load_agroup(0);
+      load_agroup(1);
+      // row statistics of the 16 query rows this lane holds
+      f32x4 l4[4], d4[4];
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int qoff = sub * 32 + 8 * r4 + 4 * g;
+        l4[r4] = lds_read16<f32x4>(stb, qoff * 4);
+        d4[r4] = lds_read16<f32x4>(stb, (C::BM + qoff) * 4);
       }
+      sched_fence();
+#pragma unroll
+      for (int gi = 0; gi < NG; ++gi) {
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          s = F::mfma(fa[gi & 1][2 * e], kf[2 * gi + e], s);
+          dp = F::mfma(fa[gi & 1][2 * e + 1], vf[2 * gi + e], dp);
+        }
+        if (gi + 2 < NG) load_agroup(gi + 2);
+        sched_fence();
+      }
+
+      // Transposed dO / Q fragments for the first 16 queries: requested before the softmax
+      // arithmetic so that they arrive while it runs.
+      v8 ft[2][2 * DT];
+      auto load_tgroup = [&](int kk) {
+        const int o = suboff + kk * 16 * C::ROWB;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          ft[kk & 1][2 * dt] = read_tr_pair<T>(dob, off.tr[0][dt] + o, off.tr[1][dt] + o);
+          ft[kk & 1][2 * dt + 1] = read_tr_pair<T>(qb, off.tr[0][dt] + o, off.tr[1][dt] + o);
+        }
+      };
+      load_tgroup(0);
+      sched_fence();
 
       float p[16], ds[16];
       const bool need_mask = CAUSAL && q0s < k0w + 31;
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int qoff = sub * 32 + 8 * r4 + 4 * g;
-        const f32x4 l4 = lds_read16<f32x4>(stb, qoff * 4);
-        const f32x4 d4 = lds_read16<f32x4>(stb, (C::BM + qoff) * 4);
+      for (int r4 = 0; r4 < 4; ++r4)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = r4 * 4 + e;
-          float pe = __builtin_amdgcn_exp2f(s[r] * scale_log2 - l4[e]);
-          if (need_mask && krow > m * C::BM + qoff + e) pe = 0.f;
+          float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, -l4[r4][e]));
+          if (need_mask && krow > q0s + 8 * r4 + 4 * g + e) pe = 0.f;
           p[r] = pe;
-          ds[r] = pe * (dp[r] - d4[e]);
+          ds[r] = pe * (dp[r] - d4[r4][e]);
         }
-      }
+      load_tgroup(1);
+      sched_fence();
 
+      // dV^T += dO^T P and dK^T += Q^T dS, 16 queries per step
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk) {
         const v8 pf = pack8<T>(&p[kk * 8]);
         const v8 dsf = pack8<T>(&ds[kk * 8]);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-          const v8 doT = read_transposed<T, C::STR>(dob, sub * 32 + 16 * kk, dt, lane);
-          dv[dt] = F::mfma(doT, pf, dv[dt]);
-          const v8 qT = read_transposed<T, C::STR>(qb, sub * 32 + 16 * kk, dt, lane);
-          dk[dt] = F::mfma(qT, dsf, dk[dt]);
+          dv[dt] = F::mfma(ft[kk & 1][2 * dt], pf, dv[dt]);
+          dk[dt] = F::mfma(ft[kk & 1][2 * dt + 1], dsf, dk[dt]);
         }
+        sched_fence();
       }
     }
 
-    if (m + 1 < ns) store_stage(buf ^ 1);
+    if (m + 1 < ns) store_stage(BUF ^ 1);
     __syncthreads();
+  };
+
+  for (int m = s_begin; m < ns; m += 2) {
+    stage(IntC<0>{}, m);
+    if (m + 1 < ns) stage(IntC<1>{}, m + 1);
   }
 
   SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
@@ -283,8 +393,8 @@ __global__ __launch_bounds__(256) void mha_bwd_dkdv_kernel(
 template <int D> struct BwdQCfg {
   static constexpr int BM = 128;  // query rows per workgroup (32 per wave)
   static constexpr int BN = 64;   // keys per iteration
-  static constexpr int STR = D * 2 + 16;
-  static constexpr int TILE = BN * STR;  // one of K, V
+  static constexpr int ROWB = D * 2;
+  static constexpr int TILE = BN * ROWB;  // one of K, V (swizzled, unpadded)
   static constexpr int STAGE = 2 * TILE;
   static constexpr int OSTR = D * 2 + 16;
   static constexpr int SMEM = 2 * STAGE;
@@ -314,8 +424,7 @@ __global__ __launch_bounds__(256) void mha_bwd_dq_kernel(
   const int qt = CAUSAL ? nqt - 1 - rank : rank;
 
   const size_t head_off = (size_t)head * N * D;
-  const T* Kh = K + head_off;
-  const T* Vh = V + head_off;
+  const BufView kview(K + head_off, (uint32_t)N * D * 2), vview(V + head_off, (uint32_t)N * D * 2);
 
   const int q0 = qt * C::BM + wave * 32;
   const int qrow = q0 + c32;
@@ -327,8 +436,8 @@ __global__ __launch_bounds__(256) void mha_bwd_dq_kernel(
     qf[ks] = *reinterpret_cast<const v8*>(Q + head_off + (size_t)qrow_c * D + ks * 16 + g * 8);
     dof[ks] = *reinterpret_cast<const v8*>(dO + head_off + (size_t)qrow_c * D + ks * 16 + g * 8);
   }
-  const float lse2 = LSE[(size_t)head * N + qrow_c] * 1.4426950408889634f;
-  const float Dq = Dws[(size_t)head * N + qrow_c];
+  float lse2 = LSE[(size_t)head * N + qrow_c] * 1.4426950408889634f;
+  float Dq = Dws[(size_t)head * N + qrow_c];
 
   int kv_end = N;
   if (CAUSAL) {
@@ -337,6 +446,8 @@ __global__ __launch_bounds__(256) void mha_bwd_dq_kernel(
   }
   const int nt = (kv_end + C::BN - 1) / C::BN;
 
+  const SwzLane<D> off(lane);
+
   u32x4 kreg[NLD], vreg[NLD];
   f32x16 dq[DT];
 #pragma unroll
@@ -344,39 +455,72 @@ __global__ __launch_bounds__(256) void mha_bwd_dq_kernel(
 #pragma unroll
     for (int r = 0; r < 16; ++r) dq[dt][r] = 0.f;
 
-  tile_g2r<D, C::BN>(Kh, 0, N, tid, kreg);
-  tile_g2r<D, C::BN>(Vh, 0, N, tid, vreg);
-  tile_r2s<D, C::BN, C::STR>(smem, tid, kreg);
-  tile_r2s<D, C::BN, C::STR>(smem + C::TILE, tid, vreg);
+  tile_b2r<D, C::BN>(kview, 0, tid, kreg);
+  tile_b2r<D, C::BN>(vview, 0, tid, vreg);
+  wait_vmem_all();  // Q / dO fragments and the row statistics are in registers before the loop
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]), "+v"(dof[ks]));
+  asm volatile("" : "+v"(lse2), "+v"(Dq));
+  tile_r2s_swz<D, C::BN>(smem, tid, kreg);
+  tile_r2s_swz<D, C::BN>(smem + C::TILE, tid, vreg);
   __syncthreads();
 
-  for (int j = 0; j < nt; ++j) {
-    const int buf = j & 1;
+  auto tile = [&](auto bufc, int j) {
+    constexpr int BUF = decltype(bufc)::value;
     if (j + 1 < nt) {
-      tile_g2r<D, C::BN>(Kh, (j + 1) * C::BN, N, tid, kreg);
-      tile_g2r<D, C::BN>(Vh, (j + 1) * C::BN, N, tid, vreg);
+      tile_b2r<D, C::BN>(kview, (j + 1) * C::BN, tid, kreg);
+      tile_b2r<D, C::BN>(vview, (j + 1) * C::BN, tid, vreg);
     }
     const int k0 = j * C::BN;
     if (!CAUSAL || k0 <= q0 + 31) {
-      SPARK_LDS const char* kb = smem + buf * C::STAGE;
+      SPARK_LDS const char* kb = smem + BUF * C::STAGE;
       SPARK_LDS const char* vb = kb + C::TILE;
+      constexpr int NG = KS / 2;
 
+      // S^T = K Q^T and dP^T = V dO^T (lane = query column, registers = keys); 8 row fragments
+      // (2 k-steps x 2 key blocks x {K, V}) are read ahead of the MFMAs that consume them.
       f32x16 s[2], dp[2];
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) { s[mt][r] = 0.f; dp[mt][r] = 0.f; }
+      v8 fa[2][8];
+      auto load_agroup = [&](int gi) {
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
+        for (int e = 0; e < 2; ++e)
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-          const int off = (mt * 32 + c32) * C::STR + ks * 32 + g * 16;
-          const v8 ka = lds_read16<v8>(kb, off);
-          s[mt] = F::mfma(ka, qf[ks], s[mt]);
-          const v8 va = lds_read16<v8>(vb, off);
-          dp[mt] = F::mfma(va, dof[ks], dp[mt]);
-        }
+          for (int mt = 0; mt < 2; ++mt) {
+            const int o = off.row[2 * gi + e] + mt * 32 * C::ROWB;
+            fa[gi & 1][4 * e + 2 * mt] = lds_read16<v8>(kb, o);
+            fa[gi & 1][4 * e + 2 * mt + 1] = lds_read16<v8>(vb, o);
+          }
+      };
+      load_agroup(0);
+      sched_fence();
+#pragma unroll
+      for (int gi = 0; gi < NG; ++gi) {
+        if (gi + 1 < NG) load_agroup(gi + 1);
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt) {
+            s[mt] = F::mfma(fa[gi & 1][4 * e + 2 * mt], qf[2 * gi + e], s[mt]);
+            dp[mt] = F::mfma(fa[gi & 1][4 * e + 2 * mt + 1], dof[2 * gi + e], dp[mt]);
+          }
+        sched_fence();
       }
+
+      // K^T fragments of the first two 16-key steps fly during the softmax arithmetic
+      v8 ft[2][DT];
+      auto load_tgroup = [&](int kk) {
+        const int o = kk * 16 * C::ROWB;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+          ft[kk & 1][dt] = read_tr_pair<T>(kb, off.tr[0][dt] + o, off.tr[1][dt] + o);
+      };
+      load_tgroup(0);
+      load_tgroup(1);
+      sched_fence();
 
       float ds[32];
       const bool need_mask = (CAUSAL && k0 + C::BN - 1 > q0) || (k0 + C::BN > N);
@@ -384,7 +528,7 @@ __global__ __launch_bounds__(256) void mha_bwd_dq_kernel(
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float pe = __builtin_amdgcn_exp2f(s[mt][r] * scale_log2 - lse2);
+          float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mt][r], scale_log2, -lse2));
           if (need_mask) {
             const int key = k0 + mt * 32 + 8 * (r / 4) + 4 * g + (r % 4);
             const bool ok = key < N && (!CAUSAL || key <= qrow);
@@ -392,22 +536,28 @@ __global__ __launch_bounds__(256) void mha_bwd_dq_kernel(
           }
           ds[mt * 16 + r] = pe * (dp[mt][r] - Dq);
         }
+      sched_fence();
 
+      // dQ^T += K^T dS^T, 16 keys per step
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
         const v8 dsf = pack8<T>(&ds[kk * 8]);
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          const v8 kT = read_transposed<T, C::STR>(kb, 16 * kk, dt, lane);
-          dq[dt] = F::mfma(kT, dsf, dq[dt]);
-        }
+        for (int dt = 0; dt < DT; ++dt) dq[dt] = F::mfma(ft[kk & 1][dt], dsf, dq[dt]);
+        if (kk + 2 < 4) load_tgroup(kk + 2);
+        sched_fence();
       }
     }
     if (j + 1 < nt) {
-      tile_r2s<D, C::BN, C::STR>(smem + (buf ^ 1) * C::STAGE, tid, kreg);
-      tile_r2s<D, C::BN, C::STR>(smem + (buf ^ 1) * C::STAGE + C::TILE, tid, vreg);
+      tile_r2s_swz<D, C::BN>(smem + (BUF ^ 1) * C::STAGE, tid, kreg);
+      tile_r2s_swz<D, C::BN>(smem + (BUF ^ 1) * C::STAGE + C::TILE, tid, vreg);
     }
     __syncthreads();
+  };
+
+  for (int j = 0; j < nt; j += 2) {
+    tile(IntC<0>{}, j);
+    if (j + 1 < nt) tile(IntC<1>{}, j + 1);
   }
 
   SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;

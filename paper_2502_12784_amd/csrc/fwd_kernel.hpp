@@ -93,16 +93,15 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
   }
   const int nt = (kv_end + C::BN - 1) / C::BN;
 
+  // Tile loads: thread t owns 16-byte chunk t of each group of 256 chunks (= 4096 bytes).
+  const BufView kview(Kh, (uint32_t)N * D * 2), vview(Vh, (uint32_t)N * D * 2);
   u32x4 kreg[NLD], vreg[NLD];
   auto load_tile = [&](int j) {
+    const uint32_t tile_off = (uint32_t)j * (C::BN * D * 2);
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      const int c = tid + 256 * i;
-      const int row = c / CPR, cc = c % CPR;
-      int grow = j * C::BN + row;
-      grow = grow < N ? grow : N - 1;
-      kreg[i] = *reinterpret_cast<const u32x4*>(Kh + (size_t)grow * D + cc * 8);
-      vreg[i] = *reinterpret_cast<const u32x4*>(Vh + (size_t)grow * D + cc * 8);
+      kreg[i] = kview.load16(tid * 16 + i * 4096, tile_off);
+      vreg[i] = vview.load16(tid * 16 + i * 4096, tile_off);
     }
   };
   auto store_tile = [&](int buf) {
@@ -124,6 +123,11 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
   float l_run = 0.f;        // running row sum over this lane's keys only (halves merged at the end)
 
   load_tile(0);
+  // The Q fragments must have arrived before the loop: otherwise the waits for them would sit
+  // inside the loop body and would also wait for the next tile's prefetch every iteration.
+  wait_vmem_all();
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]));
   store_tile(0);
   __syncthreads();
 
@@ -136,26 +140,55 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
       SPARK_LDS const char* kb = smem + buf * C::STAGE;
       SPARK_LDS const char* vb = kb + C::KBYTES;
 
-      // S^T tile: 64 keys x 32 queries
+      // S^T tile: 64 keys x 32 queries.  K fragments are read two k-steps (4 reads) ahead of
+      // the MFMAs that consume them; the fences pin that order against the scheduler, which
+      // would otherwise sink every read next to its use and serialise read -> wait -> MFMA.
       f32x16 s[2];
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[mt][r] = 0.f;
+      constexpr int NG = KS / 2;  // groups of 2 k-steps x 2 key blocks
+      v8 kf[2][4];
+      auto load_kgroup = [&](int gi) {
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
+        for (int e = 0; e < 4; ++e)
+          kf[gi & 1][e] = lds_read16<v8>(kb, ((e & 1) * 32 + c32) * C::KSTR + (2 * gi + (e >> 1)) * 32 + g * 16);
+      };
+      load_kgroup(0);
+      load_kgroup(1);
+      sched_fence();
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-          v8 kf = lds_read16<v8>(kb, (mt * 32 + c32) * C::KSTR + ks * 32 + g * 16);
-          s[mt] = F::mfma(kf, qf[ks], s[mt]);
-        }
+      for (int gi = 0; gi < NG; ++gi) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          s[e & 1] = F::mfma(kf[gi & 1][e], qf[2 * gi + (e >> 1)], s[e & 1]);
+        if (gi + 2 < NG) load_kgroup(gi + 2);
+        sched_fence();
       }
+
+      // V^T fragments of the first two 16-key steps are requested now, so that they arrive
+      // while the softmax arithmetic runs.
+      v8 vf[2][DT];
+      auto load_vgroup = [&](int kk) {
+        const int row0 = 16 * kk + 4 * g + (i16 >> 2);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          const int col = dt * 32 + (c32 & 16) + 4 * (i16 & 3);
+          const v4 lo = lds_read_tr8<v4>(vb, row0 * C::VSTR + col * 2);
+          const v4 hi = lds_read_tr8<v4>(vb, (row0 + 8) * C::VSTR + col * 2);
+          vf[kk & 1][dt] = join4<v8, v4>(lo, hi);
+        }
+      };
+      load_vgroup(0);
+      load_vgroup(1);
+      sched_fence();
 
       float t[32];
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) t[mt * 16 + r] = s[mt][r] * scale_log2;
+        for (int r = 0; r < 16; ++r) t[mt * 16 + r] = s[mt][r];
 
       const bool need_mask = (CAUSAL && k0 + C::BN - 1 > q0) || (k0 + C::BN > N);
       if (need_mask) {
@@ -169,39 +202,45 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
           }
       }
 
+      // Row max of the raw scores (scale > 0, so it commutes with the scaling).
       float mx = t[0];
 #pragma unroll
       for (int i = 1; i < 32; ++i) mx = fmaxf(mx, t[i]);
-      mx = fmaxf(mx, other_half(mx));
-      const float m_new = fmaxf(m_run, mx);
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      m_run = m_new;
+      mx = half_pair_max(mx) * scale_log2;
+
+      // Online softmax (Eq. 3) with a lazy reference point: m_run is only moved, and the
+      // accumulators only rescaled by exp(m_pre - m_cur), when some row's maximum grew by more
+      // than 2^8.  Until then P is formed against the old reference and stays <= 256, which fp32
+      // sums and the 16-bit MFMA operand hold without loss; the final O = acc / l and
+      // LSE = m + log l do not depend on which reference was used.
+      if (__any(mx > m_run + 8.0f)) {
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+      }
 
       float rs = 0.f;
 #pragma unroll
       for (int i = 0; i < 32; ++i) {
-        t[i] = __builtin_amdgcn_exp2f(t[i] - m_new);
+        t[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(t[i], scale_log2, -m_run));
         rs += t[i];
       }
-      l_run = l_run * alpha + rs;
+      l_run += rs;
 
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
-
-      // O^T += V^T P^T, 16 keys per MFMA
+      // O^T += V^T P^T, 16 keys per step, V^T fragments two steps ahead
+      sched_fence();
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
         const v8 pf = pack8<T>(&t[kk * 8]);
-        const int row0 = 16 * kk + 4 * g + (i16 >> 2);
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          const int col = dt * 32 + (c32 & 16) + 4 * (i16 & 3);
-          const v4 lo = lds_read_tr8<v4>(vb, row0 * C::VSTR + col * 2);
-          const v4 hi = lds_read_tr8<v4>(vb, (row0 + 8) * C::VSTR + col * 2);
-          o[dt] = F::mfma(join4<v8, v4>(lo, hi), pf, o[dt]);
-        }
+        for (int dt = 0; dt < DT; ++dt) o[dt] = F::mfma(vf[kk & 1][dt], pf, o[dt]);
+        if (kk + 2 < 4) load_vgroup(kk + 2);
+        sched_fence();
       }
     }
 
@@ -210,7 +249,7 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
   }
 
   // Epilogue: normalise, round once, transpose through this wave's LDS slice, store rows.
-  l_run += other_half(l_run);
+  l_run = half_pair_sum(l_run);
   const float inv = 1.0f / l_run;
   SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
 #pragma unroll

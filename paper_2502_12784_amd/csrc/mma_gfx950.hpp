@@ -85,7 +85,38 @@ static __device__ __forceinline__ typename Frag<T>::v8 pack8(const float* x) {
   return r;
 }
 
-// Value held by the lane 32 positions away (the other half of the wave).
-static __device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32); }
+// Reductions over the two lanes l and l^32 (the two halves of a wave), result in both lanes.
+// v_permlane32_swap exchanges the upper half of its first operand with the lower half of its
+// second; called with (x, x) it returns {x of the lower-half lane, x of the upper-half lane} in
+// both lanes, without going through LDS.
+static __device__ __forceinline__ float half_pair_max(float x) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__builtin_bit_cast(float, (uint32_t)r[0]), __builtin_bit_cast(float, (uint32_t)r[1]));
+}
+static __device__ __forceinline__ float half_pair_sum(float x) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __builtin_bit_cast(float, (uint32_t)r[0]) + __builtin_bit_cast(float, (uint32_t)r[1]);
+}
+
+// Raw buffer view of one row-major [rows][D] 16-bit matrix.  Loads whose 16 bytes do not lie
+// inside the matrix return zeros instead of faulting, so ragged tiles need no address clamps,
+// and the per-tile part of the address is a scalar offset (no vector address arithmetic in the
+// main loops).  The matrix must be smaller than 4 GiB.
+struct BufView {
+  __amdgpu_buffer_rsrc_t rsrc;
+  __device__ __forceinline__ BufView(const void* base, uint32_t bytes)
+      : rsrc(__builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000)) {}
+  __device__ __forceinline__ u32x4 load16(uint32_t lane_off, uint32_t tile_off) const {
+    return __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane_off, tile_off, 0);
+  }
+};
+
+// Nothing may be moved across this point by the instruction scheduler.
+static __device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
+
+// s_waitcnt vmcnt(0): every outstanding global/buffer load of this wave has returned.
+static __device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 }  // namespace spark
