@@ -194,16 +194,17 @@ template <int D> struct BwdKvCfg {
   static constexpr int BM = 64;   // query rows per LDS stage (two 32-row steps)
   static constexpr int ROWB = D * 2;       // bytes per (swizzled, unpadded) row
   static constexpr int TILE = BM * ROWB;   // one of Q, dO
-  static constexpr int STAT = 2 * BM * 4;  // LSE*log2(e) and D of the stage's rows
-  static constexpr int STAGE = 2 * TILE;   // tiles only; LDS = [stat 0 | stat 1 | stage 0 | stage 1]
+  static constexpr int STAGE = 2 * TILE;   // power of two: the buffer is switched by one XOR
+  static constexpr int STAT = 2 * BM * 4;  // -LSE/scale and -D of the stage's rows
   static constexpr int OSTR = D * 2 + 16;
-  static constexpr int SMEM = 2 * STAT + 2 * STAGE;
+  // LDS = [stage 0 | stage 1 | stat 0 | stat 1]
+  static constexpr int SMEM = 2 * STAGE + 2 * STAT;
+  static_assert((STAGE & (STAGE - 1)) == 0 && (STAT & (STAT - 1)) == 0, "XOR buffer switch");
   static_assert(4 * 32 * OSTR <= SMEM, "epilogue staging must fit");
-  static_assert(2 * STAGE <= 65536, "tile displacements must fit the 16-bit offset field");
 };
 
 template <typename T, int D, bool CAUSAL>
-__global__ __launch_bounds__(256) void mha_bwd_dkdv_kernel(
+__global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Dws,
     T* __restrict__ dK, T* __restrict__ dV, int N, int nkt, float scale, float scale_log2) {
@@ -248,7 +249,10 @@ __global__ __launch_bounds__(256) void mha_bwd_dkdv_kernel(
   const int ns = (N + C::BM - 1) / C::BM;                 // query stages in the sequence
   const int s_begin = CAUSAL ? (kt * C::BN) / C::BM : 0;  // earlier queries see none of this tile
 
-  const SwzLane<D> off(lane, 2 * C::STAT);  // offsets relative to smem, tiles start after the stats
+  // Per-lane LDS read offsets of the current buffer; switching buffers is one XOR each.
+  SwzLane<D> off(lane);
+  int stat_off = 2 * C::STAGE + 16 * g;  // float4 of rows 4g.. in the current stat block
+  const float neg_inv_scale = -1.0f / scale;
 
   u32x4 qreg[NLD], doreg[NLD];
   float statreg = 0.f;
@@ -257,17 +261,20 @@ __global__ __launch_bounds__(256) void mha_bwd_dkdv_kernel(
     tile_b2r<D, C::BM>(doview, m * C::BM, tid, doreg);
     if (tid < 2 * C::BM) {
       const int row = m * C::BM + (tid & (C::BM - 1));
-      if (tid < C::BM)  // rows past the end get LSE = +inf so that P = 0 there
-        statreg = row < N ? LSEh[row] * 1.4426950408889634f : INFINITY;
+      // The statistics are stored negated and in the units of the raw scores, so that they
+      // can initialise the MFMA accumulators: S - LSE/scale and dP - D come out of the
+      // contractions directly.  Rows past the end get -inf (P = 0 there) and D = 0.
+      if (tid < C::BM)
+        statreg = row < N ? LSEh[row] * neg_inv_scale : -INFINITY;
       else
-        statreg = row < N ? Dh[row] : 0.f;
+        statreg = row < N ? -Dh[row] : 0.f;
     }
   };
   auto store_stage = [&](int buf) {
-    SPARK_LDS char* sb = smem + 2 * C::STAT + buf * C::STAGE;
+    SPARK_LDS char* sb = smem + buf * C::STAGE;
     tile_r2s_swz<D, C::BM>(sb, tid, qreg);
     tile_r2s_swz<D, C::BM>(sb + C::TILE, tid, doreg);
-    if (tid < 2 * C::BM) lds_write(smem + buf * C::STAT, tid * 4, statreg);
+    if (tid < 2 * C::BM) lds_write(smem + 2 * C::STAGE + buf * C::STAT, tid * 4, statreg);
   };
 
   load_stage(s_begin);
@@ -277,15 +284,12 @@ __global__ __launch_bounds__(256) void mha_bwd_dkdv_kernel(
   store_stage(0);
   __syncthreads();
 
-  // One LDS stage (64 queries) in buffer BUF; the next stage's global loads are in flight
-  // meanwhile and are written to the other buffer at the end.
-  auto stage = [&](auto bufc, int m) {
-    constexpr int BUF = decltype(bufc)::value;
+  for (int m = s_begin; m < ns; ++m) {
+    const int buf = (m - s_begin) & 1;
     if (m + 1 < ns) load_stage(m + 1);
 
-    SPARK_LDS const char* qb = smem + BUF * C::STAGE;  // + off.* (which include the stats bias)
-    SPARK_LDS const char* dob = qb + C::TILE;
-    SPARK_LDS const char* stb = smem + BUF * C::STAT;
+    SPARK_LDS const char* qb = smem;             // + off.* (which carry the buffer bit)
+    SPARK_LDS const char* dob = smem + C::TILE;
 
 #pragma unroll
     for (int sub = 0; sub < C::BM / 32; ++sub) {
@@ -295,11 +299,9 @@ __global__ __launch_bounds__(256) void mha_bwd_dkdv_kernel(
       constexpr int NG = KS / 2;
       const int suboff = sub * 32 * C::ROWB;
 
-      // S = Q K^T and dP = dO V^T (lane = key column, registers = query rows); the Q / dO row
+      // S - LSE/scale = Q K^T - LSE/scale and dP - D = dO V^T - D (lane = key column, registers
+      // = query rows): the accumulators start from the negated row statistics.  Q / dO row
       // fragments are read two k-steps ahead of the MFMAs that consume them.
-      f32x16 s, dp;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
       v8 fa[2][4];
       auto load_agroup = [&](int gi) {
 #pragma unroll
@@ -309,15 +311,16 @@ __global__ __launch_bounds__(256) void mha_bwd_dkdv_kernel(
         }
       };
       load_agroup(0);
-      load_agroup(1);
-      // row statistics of the 16 query rows this lane holds
-      f32x4 l4[4], d4[4];
+      f32x16 s, dp;
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
-        const int qoff = sub * 32 + 8 * r4 + 4 * g;
-        l4[r4] = lds_read16<f32x4>(stb, qoff * 4);
-        d4[r4] = lds_read16<f32x4>(stb, (C::BM + qoff) * 4);
+        const int o = stat_off + (sub * 32 + 8 * r4) * 4;
+        const f32x4 l4 = lds_read16<f32x4>(smem, o);
+        const f32x4 d4 = lds_read16<f32x4>(smem, o + C::BM * 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { s[r4 * 4 + e] = l4[e]; dp[r4 * 4 + e] = d4[e]; }
       }
+      load_agroup(1);
       sched_fence();
 #pragma unroll
       for (int gi = 0; gi < NG; ++gi) {
@@ -330,56 +333,65 @@ __global__ __launch_bounds__(256) void mha_bwd_dkdv_kernel(
         sched_fence();
       }
 
-      // Transposed dO / Q fragments for the first 16 queries: requested before the softmax
-      // arithmetic so that they arrive while it runs.
-      v8 ft[2][2 * DT];
-      auto load_tgroup = [&](int kk) {
+      // Transposed dO / Q fragments, 4 at a time (one 16-query step of two d-tiles), two groups
+      // ahead of the MFMAs; the first two groups are requested before the softmax arithmetic.
+      constexpr int NTG = 2 * (DT / 2);  // groups: (kk, dt pair)
+      v8 ft[2][4];
+      auto load_tgroup = [&](int tg) {
+        const int kk = tg / (DT / 2), dt0 = 2 * (tg % (DT / 2));
         const int o = suboff + kk * 16 * C::ROWB;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          ft[kk & 1][2 * dt] = read_tr_pair<T>(dob, off.tr[0][dt] + o, off.tr[1][dt] + o);
-          ft[kk & 1][2 * dt + 1] = read_tr_pair<T>(qb, off.tr[0][dt] + o, off.tr[1][dt] + o);
+        for (int e = 0; e < 2; ++e) {
+          ft[tg & 1][2 * e] = read_tr_pair<T>(dob, off.tr[0][dt0 + e] + o, off.tr[1][dt0 + e] + o);
+          ft[tg & 1][2 * e + 1] = read_tr_pair<T>(qb, off.tr[0][dt0 + e] + o, off.tr[1][dt0 + e] + o);
         }
       };
       load_tgroup(0);
+      load_tgroup(1);
       sched_fence();
+      asm volatile("" : "+v"(s), "+v"(dp));  // keep the score tiles in VALU-readable registers
 
       float p[16], ds[16];
       const bool need_mask = CAUSAL && q0s < k0w + 31;
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int r = r4 * 4 + e;
-          float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, -l4[r4][e]));
-          if (need_mask && krow > q0s + 8 * r4 + 4 * g + e) pe = 0.f;
-          p[r] = pe;
-          ds[r] = pe * (dp[r] - d4[r4][e]);
-        }
-      load_tgroup(1);
-      sched_fence();
-
-      // dV^T += dO^T P and dK^T += Q^T dS, 16 queries per step
+      for (int r = 0; r < 16; ++r) {
+        float pe = __builtin_amdgcn_exp2f(s[r] * scale_log2);
+        if (need_mask && krow > q0s + 8 * (r / 4) + 4 * g + (r % 4)) pe = 0.f;
+        p[r] = pe;
+        ds[r] = pe * dp[r];
+      }
+      v8 pf[2], dsf[2];
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk) {
-        const v8 pf = pack8<T>(&p[kk * 8]);
-        const v8 dsf = pack8<T>(&ds[kk * 8]);
+        pf[kk] = pack8<T>(&p[kk * 8]);
+        dsf[kk] = pack8<T>(&ds[kk * 8]);
+      }
+      sched_fence();
+
+      // dV^T += dO^T P and dK^T += Q^T dS
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          dv[dt] = F::mfma(ft[kk & 1][2 * dt], pf, dv[dt]);
-          dk[dt] = F::mfma(ft[kk & 1][2 * dt + 1], dsf, dk[dt]);
+      for (int tg = 0; tg < NTG; ++tg) {
+        const int kk = tg / (DT / 2), dt0 = 2 * (tg % (DT / 2));
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          dv[dt0 + e] = F::mfma(ft[tg & 1][2 * e], pf[kk], dv[dt0 + e]);
+          dk[dt0 + e] = F::mfma(ft[tg & 1][2 * e + 1], dsf[kk], dk[dt0 + e]);
         }
+        if (tg + 2 < NTG) load_tgroup(tg + 2);
         sched_fence();
       }
     }
 
-    if (m + 1 < ns) store_stage(BUF ^ 1);
+    if (m + 1 < ns) store_stage(buf ^ 1);
+    // switch the read offsets to the other buffer
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) off.row[ks] ^= C::STAGE;
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) off.tr[h][dt] ^= C::STAGE;
+    stat_off ^= C::STAT;
     __syncthreads();
-  };
-
-  for (int m = s_begin; m < ns; m += 2) {
-    stage(IntC<0>{}, m);
-    if (m + 1 < ns) stage(IntC<1>{}, m + 1);
   }
 
   SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
@@ -392,17 +404,19 @@ __global__ __launch_bounds__(256) void mha_bwd_dkdv_kernel(
 // ---------------------------------------------------------------------------------------
 template <int D> struct BwdQCfg {
   static constexpr int BM = 128;  // query rows per workgroup (32 per wave)
-  static constexpr int BN = 64;   // keys per iteration
+  // keys per iteration: 32 at D = 128 keeps the kernel within 256 registers, so that two
+  // workgroups share a CU and one hides the other's softmax arithmetic and LDS latency
+  static constexpr int BN = D == 128 ? 32 : 64;
   static constexpr int ROWB = D * 2;
   static constexpr int TILE = BN * ROWB;  // one of K, V (swizzled, unpadded)
-  static constexpr int STAGE = 2 * TILE;
+  static constexpr int STAGE = 2 * TILE;  // power of two: the buffer is switched by one XOR
   static constexpr int OSTR = D * 2 + 16;
-  static constexpr int SMEM = 2 * STAGE;
-  static_assert(4 * 32 * OSTR <= SMEM, "epilogue staging must fit");
+  static constexpr int SMEM = 2 * STAGE > 4 * 32 * OSTR ? 2 * STAGE : 4 * 32 * OSTR;  // tiles / epilogue
+  static_assert((STAGE & (STAGE - 1)) == 0, "XOR buffer switch");
 };
 
 template <typename T, int D, bool CAUSAL>
-__global__ __launch_bounds__(256) void mha_bwd_dq_kernel(
+__global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Dws,
     T* __restrict__ dQ, int N, int nqt, float scale, float scale_log2) {
@@ -446,7 +460,7 @@ __global__ __launch_bounds__(256) void mha_bwd_dq_kernel(
   }
   const int nt = (kv_end + C::BN - 1) / C::BN;
 
-  const SwzLane<D> off(lane);
+  SwzLane<D> off(lane);  // read offsets of the current buffer; switched by one XOR each
 
   u32x4 kreg[NLD], vreg[NLD];
   f32x16 dq[DT];
@@ -465,52 +479,50 @@ __global__ __launch_bounds__(256) void mha_bwd_dq_kernel(
   tile_r2s_swz<D, C::BN>(smem + C::TILE, tid, vreg);
   __syncthreads();
 
-  auto tile = [&](auto bufc, int j) {
-    constexpr int BUF = decltype(bufc)::value;
+  for (int j = 0; j < nt; ++j) {
+    const int buf = j & 1;
     if (j + 1 < nt) {
       tile_b2r<D, C::BN>(kview, (j + 1) * C::BN, tid, kreg);
       tile_b2r<D, C::BN>(vview, (j + 1) * C::BN, tid, vreg);
     }
     const int k0 = j * C::BN;
     if (!CAUSAL || k0 <= q0 + 31) {
-      SPARK_LDS const char* kb = smem + BUF * C::STAGE;
-      SPARK_LDS const char* vb = kb + C::TILE;
-      constexpr int NG = KS / 2;
+      SPARK_LDS const char* kb = smem;  // + off.* (which carry the buffer bit)
+      SPARK_LDS const char* vb = smem + C::TILE;
 
-      // S^T = K Q^T and dP^T = V dO^T (lane = query column, registers = keys); 8 row fragments
-      // (2 k-steps x 2 key blocks x {K, V}) are read ahead of the MFMAs that consume them.
-      f32x16 s[2], dp[2];
+      // S^T = K Q^T and dP^T = V dO^T (lane = query column, registers = keys); the row
+      // fragments of one k-step (MT key blocks x {K, V}) are read two steps ahead of the MFMAs.
+      constexpr int MT = C::BN / 32;  // 32-key blocks per tile
+      f32x16 s[MT], dp[MT];
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
+      for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) { s[mt][r] = 0.f; dp[mt][r] = 0.f; }
-      v8 fa[2][8];
-      auto load_agroup = [&](int gi) {
+      v8 fa[2][2 * MT];
+      auto load_agroup = [&](int ks) {
 #pragma unroll
-        for (int e = 0; e < 2; ++e)
-#pragma unroll
-          for (int mt = 0; mt < 2; ++mt) {
-            const int o = off.row[2 * gi + e] + mt * 32 * C::ROWB;
-            fa[gi & 1][4 * e + 2 * mt] = lds_read16<v8>(kb, o);
-            fa[gi & 1][4 * e + 2 * mt + 1] = lds_read16<v8>(vb, o);
-          }
+        for (int mt = 0; mt < MT; ++mt) {
+          const int o = off.row[ks] + mt * 32 * C::ROWB;
+          fa[ks & 1][2 * mt] = lds_read16<v8>(kb, o);
+          fa[ks & 1][2 * mt + 1] = lds_read16<v8>(vb, o);
+        }
       };
       load_agroup(0);
+      load_agroup(1);
       sched_fence();
 #pragma unroll
-      for (int gi = 0; gi < NG; ++gi) {
-        if (gi + 1 < NG) load_agroup(gi + 1);
+      for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
-        for (int e = 0; e < 2; ++e)
-#pragma unroll
-          for (int mt = 0; mt < 2; ++mt) {
-            s[mt] = F::mfma(fa[gi & 1][4 * e + 2 * mt], qf[2 * gi + e], s[mt]);
-            dp[mt] = F::mfma(fa[gi & 1][4 * e + 2 * mt + 1], dof[2 * gi + e], dp[mt]);
-          }
+        for (int mt = 0; mt < MT; ++mt) {
+          s[mt] = F::mfma(fa[ks & 1][2 * mt], qf[ks], s[mt]);
+          dp[mt] = F::mfma(fa[ks & 1][2 * mt + 1], dof[ks], dp[mt]);
+        }
+        if (ks + 2 < KS) load_agroup(ks + 2);
         sched_fence();
       }
 
       // K^T fragments of the first two 16-key steps fly during the softmax arithmetic
+      constexpr int NKK = C::BN / 16;
       v8 ft[2][DT];
       auto load_tgroup = [&](int kk) {
         const int o = kk * 16 * C::ROWB;
@@ -522,10 +534,10 @@ __global__ __launch_bounds__(256) void mha_bwd_dq_kernel(
       load_tgroup(1);
       sched_fence();
 
-      float ds[32];
+      float ds[16 * MT];
       const bool need_mask = (CAUSAL && k0 + C::BN - 1 > q0) || (k0 + C::BN > N);
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
+      for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mt][r], scale_log2, -lse2));
@@ -536,28 +548,31 @@ __global__ __launch_bounds__(256) void mha_bwd_dq_kernel(
           }
           ds[mt * 16 + r] = pe * (dp[mt][r] - Dq);
         }
+      v8 dsf[NKK];
+#pragma unroll
+      for (int kk = 0; kk < NKK; ++kk) dsf[kk] = pack8<T>(&ds[kk * 8]);
       sched_fence();
 
       // dQ^T += K^T dS^T, 16 keys per step
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const v8 dsf = pack8<T>(&ds[kk * 8]);
+      for (int kk = 0; kk < NKK; ++kk) {
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) dq[dt] = F::mfma(ft[kk & 1][dt], dsf, dq[dt]);
-        if (kk + 2 < 4) load_tgroup(kk + 2);
+        for (int dt = 0; dt < DT; ++dt) dq[dt] = F::mfma(ft[kk & 1][dt], dsf[kk], dq[dt]);
+        if (kk + 2 < NKK) load_tgroup(kk + 2);
         sched_fence();
       }
     }
     if (j + 1 < nt) {
-      tile_r2s_swz<D, C::BN>(smem + (BUF ^ 1) * C::STAGE, tid, kreg);
-      tile_r2s_swz<D, C::BN>(smem + (BUF ^ 1) * C::STAGE + C::TILE, tid, vreg);
+      tile_r2s_swz<D, C::BN>(smem + (buf ^ 1) * C::STAGE, tid, kreg);
+      tile_r2s_swz<D, C::BN>(smem + (buf ^ 1) * C::STAGE + C::TILE, tid, vreg);
     }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) off.row[ks] ^= C::STAGE;
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) off.tr[h][dt] ^= C::STAGE;
     __syncthreads();
-  };
-
-  for (int j = 0; j < nt; j += 2) {
-    tile(IntC<0>{}, j);
-    if (j + 1 < nt) tile(IntC<1>{}, j + 1);
   }
 
   SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
