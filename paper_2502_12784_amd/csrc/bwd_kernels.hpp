@@ -400,6 +400,281 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
+// dK, dV at d = 128: software-pipelined variant.
+//
+// At d = 128 the accumulators (dK^T, dV^T: 128 registers) and the resident K / V fragments
+// (64) leave room for one wave per SIMD only, so nothing but the wave itself can hide its
+// softmax arithmetic and LDS latency.  The loop is therefore skewed by one 32-query step:
+// while the VALU turns the scores of step i into P and dS, the matrix cores already compute
+// the scores of step i+1; the dV / dK MFMAs of step i follow.  Because step i+1 may lie in the
+// next 64-query stage, stages live in a ring of three LDS slots (stage m+1 is resident while
+// stage m is processed, stage m+2 is in flight in registers).  No step is skipped: blocks above
+// the causal diagonal are masked to zero (first two stages of a workgroup only), rows past the
+// end of the sequence have P = 0 through their statistics.
+// ---------------------------------------------------------------------------------------
+template <int D> struct BwdKvPipeCfg {
+  static constexpr int BN = 128, BM = 64, SLOTS = 3;
+  static constexpr int ROWB = D * 2;
+  static constexpr int TILE = BM * ROWB;
+  static constexpr int STAGE = 2 * TILE;
+  static constexpr int STAT = 2 * BM * 4;
+  static constexpr int OSTR = D * 2 + 16;
+  static constexpr int STAT0 = SLOTS * STAGE;  // LDS = [slot 0..2 | stat 0..2]
+  static constexpr int SMEM = SLOTS * STAGE + SLOTS * STAT;
+  static_assert(4 * 32 * OSTR <= SLOTS * STAGE, "epilogue staging must fit");
+};
+
+#define SPARK_SGB_MFMA(n) __builtin_amdgcn_sched_group_barrier(0x008, n, 0)
+#define SPARK_SGB_VALU(n) __builtin_amdgcn_sched_group_barrier(0x002, n, 0)
+#define SPARK_SGB_DSR(n) __builtin_amdgcn_sched_group_barrier(0x100, n, 0)
+
+template <typename T, int D, bool CAUSAL>
+__global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+    const T* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Dws,
+    T* __restrict__ dK, T* __restrict__ dV, int N, int nkt, float scale, float scale_log2) {
+  using F = Frag<T>;
+  using v8 = typename F::v8;
+  using C = BwdKvPipeCfg<D>;
+  constexpr int KS = D / 16, DT = D / 32;
+  constexpr int NLD = C::BM * (D / 8) / 256;
+
+  extern __shared__ __attribute__((aligned(16))) char smem_generic[];
+  SPARK_LDS char* smem = (SPARK_LDS char*)smem_generic;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 5, c32 = lane & 31;
+
+  const int logical = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int head = logical / nkt;
+  const int kt = logical - head * nkt;
+
+  const size_t head_off = (size_t)head * N * D;
+  const float* LSEh = LSE + (size_t)head * N;
+  const float* Dh = Dws + (size_t)head * N;
+  const BufView qview(Q + head_off, (uint32_t)N * D * 2), doview(dO + head_off, (uint32_t)N * D * 2);
+
+  const int k0w = kt * C::BN + wave * 32;
+  const int krow = k0w + c32;
+  const int krow_c = krow < N ? krow : N - 1;
+
+  v8 kf[KS], vf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    kf[ks] = *reinterpret_cast<const v8*>(K + head_off + (size_t)krow_c * D + ks * 16 + g * 8);
+    vf[ks] = *reinterpret_cast<const v8*>(V + head_off + (size_t)krow_c * D + ks * 16 + g * 8);
+  }
+
+  f32x16 dk[DT], dv[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dk[dt][r] = 0.f; dv[dt][r] = 0.f; }
+
+  const int ns = (N + C::BM - 1) / C::BM;
+  const int s_begin = CAUSAL ? (kt * C::BN) / C::BM : 0;
+
+  const SwzLane<D> lane_off(lane);       // offsets inside slot 0
+  const int lane_stat = C::STAT0 + 16 * g;
+  const float neg_inv_scale = -1.0f / scale;
+
+  u32x4 qreg[NLD], doreg[NLD];
+  float statreg = 0.f;
+  auto load_stage = [&](int m) {  // global -> registers
+    tile_b2r<D, C::BM>(qview, m * C::BM, tid, qreg);
+    tile_b2r<D, C::BM>(doview, m * C::BM, tid, doreg);
+    if (tid < 2 * C::BM) {
+      const int row = m * C::BM + (tid & (C::BM - 1));
+      if (tid < C::BM)
+        statreg = row < N ? LSEh[row] * neg_inv_scale : -INFINITY;
+      else
+        statreg = row < N ? -Dh[row] : 0.f;
+    }
+  };
+  auto store_stage = [&](int slot) {  // registers -> LDS slot
+    SPARK_LDS char* sb = smem + slot * C::STAGE;
+    tile_r2s_swz<D, C::BM>(sb, tid, qreg);
+    tile_r2s_swz<D, C::BM>(sb + C::TILE, tid, doreg);
+    if (tid < 2 * C::BM) lds_write(smem + C::STAT0 + slot * C::STAT, tid * 4, statreg);
+  };
+
+  // score fragments of the step whose S / dP are being formed (row reads) ...
+  int rowA[KS], statA;
+  // ... and of the step whose dV / dK are being accumulated (transposing reads)
+  int trC[2][DT];
+  auto point_A = [&](int slot) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) rowA[ks] = lane_off.row[ks] + slot * C::STAGE;
+    statA = lane_stat + slot * C::STAT;
+  };
+  auto point_C = [&](int slot) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) trC[h][dt] = lane_off.tr[h][dt] + slot * C::STAGE;
+  };
+
+  // S - LSE/scale and dP - D of one 32-query step (sub = 0/1 inside the stage rowA points to)
+  v8 fa[2][4];
+  auto load_agroup = [&](int gi, int sub) {
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      fa[gi & 1][2 * e] = lds_read16<v8>(smem, rowA[2 * gi + e] + sub * 32 * C::ROWB);
+      fa[gi & 1][2 * e + 1] = lds_read16<v8>(smem + C::TILE, rowA[2 * gi + e] + sub * 32 * C::ROWB);
+    }
+  };
+  auto init_scores = [&](f32x16& s, f32x16& dp, int sub) {
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      const int o = statA + (sub * 32 + 8 * r4) * 4;
+      const f32x4 l4 = lds_read16<f32x4>(smem, o);
+      const f32x4 d4 = lds_read16<f32x4>(smem, o + C::BM * 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { s[r4 * 4 + e] = l4[e]; dp[r4 * 4 + e] = d4[e]; }
+    }
+  };
+  auto mfma_agroup = [&](f32x16& s, f32x16& dp, int gi) {
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      s = F::mfma(fa[gi & 1][2 * e], kf[2 * gi + e], s);
+      dp = F::mfma(fa[gi & 1][2 * e + 1], vf[2 * gi + e], dp);
+    }
+  };
+  constexpr int NG = KS / 2;
+  constexpr int NTG = 2 * (DT / 2);
+  v8 ft[2][4];
+  auto load_tgroup = [&](int tg, int sub) {
+    const int kk = tg / (DT / 2), dt0 = 2 * (tg % (DT / 2));
+    const int o = sub * 32 * C::ROWB + kk * 16 * C::ROWB;
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      ft[tg & 1][2 * e] = read_tr_pair<T>(smem + C::TILE, trC[0][dt0 + e] + o, trC[1][dt0 + e] + o);
+      ft[tg & 1][2 * e + 1] = read_tr_pair<T>(smem, trC[0][dt0 + e] + o, trC[1][dt0 + e] + o);
+    }
+  };
+
+  // One element of P and dS from finished scores (a few VALU instructions: the unit that is
+  // interleaved between two MFMAs of the next step's score contraction).
+  float p[16], ds[16];
+  auto softmax_elem = [&](const f32x16& s, const f32x16& dp, int r, int q0s, bool mask) {
+    float pe = __builtin_amdgcn_exp2f(s[r] * scale_log2);
+    if (mask) pe = krow > q0s + 8 * (r / 4) + 4 * g + (r % 4) ? 0.f : pe;
+    p[r] = pe;
+    ds[r] = pe * dp[r];
+  };
+
+  // ---- prologue: stages s_begin and s_begin+1 resident, scores of the first step formed ----
+  load_stage(s_begin);
+  wait_vmem_all();
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(kf[ks]), "+v"(vf[ks]));
+  store_stage(0);
+  if (s_begin + 1 < ns) {
+    load_stage(s_begin + 1);
+    store_stage(1);
+  }
+  __syncthreads();
+
+  point_A(0);
+  point_C(0);
+  f32x16 sX, dpX, sY, dpY;
+  init_scores(sX, dpX, 0);
+  load_agroup(0, 0);
+  load_agroup(1, 0);
+#pragma unroll
+  for (int gi = 0; gi < NG; ++gi) {
+    mfma_agroup(sX, dpX, gi);
+    if (gi + 2 < NG) load_agroup(gi + 2, 0);
+    sched_fence();
+  }
+
+  // One stage: steps (m, 0) and (m, 1).  On entry sX / dpX hold the scores of (m, 0), rowA
+  // points at stage m and trC at stage m; on exit sX / dpX hold the scores of (m+1, 0).
+  auto stage = [&](int m, int slot, bool mask) {
+    if (m + 2 < ns) load_stage(m + 2);
+    const int slot1 = slot == 2 ? 0 : slot + 1;
+    const int slot2 = slot1 == 2 ? 0 : slot1 + 1;
+
+    // The two halves of a stage differ only in which score registers are produced / consumed
+    // and in where the next scores come from.
+    auto half = [&](f32x16& s_new, f32x16& dp_new, int sub_new, const f32x16& s_cur,
+                    const f32x16& dp_cur, int sub_cur) {
+      // ---- scores of the next step  ||  P, dS of the current step ----
+      // 16 units of {1 MFMA, 1 softmax element, a share of the LDS reads}; the fences keep the
+      // units apart so that VALU work sits between consecutive MFMAs.
+      load_tgroup(0, sub_cur);
+#pragma unroll
+      for (int i = 0; i < 4 * NG; ++i) {
+        const int gi = i / 4, e = (i / 2) & 1;
+        if ((i & 1) == 0)
+          s_new = F::mfma(fa[gi & 1][2 * e], kf[2 * gi + e], s_new);
+        else
+          dp_new = F::mfma(fa[gi & 1][2 * e + 1], vf[2 * gi + e], dp_new);
+        if ((i & 3) == 3 && gi + 2 < NG) load_agroup(gi + 2, sub_new);
+        if (i == 2 * NG) load_tgroup(1, sub_cur);
+        softmax_elem(s_cur, dp_cur, i, m * C::BM + sub_cur * 32, mask);
+        sched_fence();
+      }
+      v8 pf[2], dsf[2];
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        pf[kk] = pack8<T>(&p[kk * 8]);
+        dsf[kk] = pack8<T>(&ds[kk * 8]);
+      }
+      // ---- dV, dK of the current step; operands of the step after next are requested ----
+#pragma unroll
+      for (int tg = 0; tg < NTG; ++tg) {
+        const int kk = tg / (DT / 2), dt0 = 2 * (tg % (DT / 2));
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          dv[dt0 + e] = F::mfma(ft[tg & 1][2 * e], pf[kk], dv[dt0 + e]);
+          dk[dt0 + e] = F::mfma(ft[tg & 1][2 * e + 1], dsf[kk], dk[dt0 + e]);
+        }
+        if (tg + 2 < NTG) load_tgroup(tg + 2, sub_cur);
+        sched_fence();
+      }
+    };
+
+    // (m, 1) scores  ||  (m, 0) softmax; then (m, 0) dV / dK
+    init_scores(sY, dpY, 1);
+    load_agroup(0, 1);
+    load_agroup(1, 1);
+    sched_fence();
+    half(sY, dpY, 1, sX, dpX, 0);
+    // (m+1, 0) scores  ||  (m, 1) softmax; then (m, 1) dV / dK
+    point_A(slot1);
+    init_scores(sX, dpX, 0);
+    load_agroup(0, 0);
+    load_agroup(1, 0);
+    sched_fence();
+    half(sX, dpX, 0, sY, dpY, 1);
+
+    // stage m+2 goes into the slot that stage m-1 used; everybody left that slot before the
+    // previous barrier
+    if (m + 2 < ns) store_stage(slot2);
+    point_C(slot1);
+    __syncthreads();
+  };
+
+  int m = s_begin, slot = 0;
+  if (CAUSAL) {  // the diagonal crosses the first two stages only
+    const int m_end = s_begin + 2 < ns ? s_begin + 2 : ns;
+    for (; m < m_end; ++m) {
+      stage(m, slot, true);
+      slot = slot == 2 ? 0 : slot + 1;
+    }
+  }
+  for (; m < ns; ++m) {
+    stage(m, slot, false);
+    slot = slot == 2 ? 0 : slot + 1;
+  }
+
+  SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
+  store_transposed<T, D, C::OSTR>(dk, scale, ob, dK + head_off, k0w, N, lane);
+  store_transposed<T, D, C::OSTR>(dv, 1.0f, ob, dV + head_off, k0w, N, lane);
+}
+
+// ---------------------------------------------------------------------------------------
 // dQ
 // ---------------------------------------------------------------------------------------
 template <int D> struct BwdQCfg {

@@ -72,7 +72,17 @@ int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const
     hipLaunchKernelGGL((mha_bwd_dot_kernel<T, D>), dim3(grid), dim3(256), 0, st, o, dout, Dws, rows);
     if (hipGetLastError() != hipSuccess || !mark(1)) return SPARK_ERR_LAUNCH;
   }
-  {  // dK, dV: one workgroup per tile of 128 keys
+  if constexpr (D == 128) {  // dK, dV: one workgroup per tile of 128 keys, software-pipelined
+    using C = BwdKvPipeCfg<D>;
+    auto kernel = mha_bwd_dkdv_pipe_kernel<T, D, CAUSAL>;
+    static const int attr = set_smem(kernel, C::SMEM);
+    if (attr != SPARK_OK) return attr;
+    const int nkt = (N + C::BN - 1) / C::BN;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * nkt)), dim3(256), C::SMEM, st, q, k, v, dout,
+                       LSE, Dws, static_cast<T*>(dK), static_cast<T*>(dV), N, nkt, scale,
+                       scale_log2);
+    if (hipGetLastError() != hipSuccess || !mark(2)) return SPARK_ERR_LAUNCH;
+  } else {  // dK, dV: one workgroup per tile of 128 keys, two workgroups per CU
     using C = BwdKvCfg<D>;
     auto kernel = mha_bwd_dkdv_kernel<T, D, CAUSAL>;
     static const int attr = set_smem(kernel, C::SMEM);
