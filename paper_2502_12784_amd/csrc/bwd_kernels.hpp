@@ -220,15 +220,22 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, c32 = lane & 31;
 
+  const int items = causal_items<CAUSAL>(nkt);  // causal: key tiles (p, nkt-1-p) are paired
   const int logical = xcd_contiguous(blockIdx.x, gridDim.x);
-  const int head = logical / nkt;
-  const int kt = logical - head * nkt;  // causal: low key tiles (most queries) come first
+  const int head = logical / items;
+  const int item = logical - head * items;
 
   const size_t head_off = (size_t)head * N * D;
   const float* LSEh = LSE + (size_t)head * N;
   const float* Dh = Dws + (size_t)head * N;
   const BufView qview(Q + head_off, (uint32_t)N * D * 2), doview(dO + head_off, (uint32_t)N * D * 2);
 
+  for (int rep = 0; rep < (CAUSAL ? 2 : 1); ++rep) {
+  const int kt = CAUSAL ? (rep == 0 ? item : nkt - 1 - item) : item;  // the long tile first
+  if (CAUSAL && rep == 1) {
+    if (kt == item) break;  // odd tile count: the middle tile has no partner
+    __syncthreads();        // the first tile's epilogue is done with the LDS
+  }
   const int k0w = kt * C::BN + wave * 32;  // first key of this wave
   const int krow = k0w + c32;
   const int krow_c = krow < N ? krow : N - 1;
@@ -264,17 +271,19 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_kernel(
       // The statistics are stored negated and in the units of the raw scores, so that they
       // can initialise the MFMA accumulators: S - LSE/scale and dP - D come out of the
       // contractions directly.  Rows past the end get -inf (P = 0 there) and D = 0.
+      // raw values only: any arithmetic on them here would force a wait for the loads
       if (tid < C::BM)
-        statreg = row < N ? LSEh[row] * neg_inv_scale : -INFINITY;
+        statreg = row < N ? LSEh[row] : INFINITY;
       else
-        statreg = row < N ? -Dh[row] : 0.f;
+        statreg = row < N ? Dh[row] : 0.f;
     }
   };
   auto store_stage = [&](int buf) {
     SPARK_LDS char* sb = smem + buf * C::STAGE;
     tile_r2s_swz<D, C::BM>(sb, tid, qreg);
     tile_r2s_swz<D, C::BM>(sb + C::TILE, tid, doreg);
-    if (tid < 2 * C::BM) lds_write(smem + 2 * C::STAGE + buf * C::STAT, tid * 4, statreg);
+    if (tid < 2 * C::BM)
+      lds_write(smem + 2 * C::STAGE + buf * C::STAT, tid * 4, statreg * (tid < C::BM ? neg_inv_scale : -1.0f));
   };
 
   load_stage(s_begin);
@@ -397,6 +406,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_kernel(
   SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
   store_transposed<T, D, C::OSTR>(dk, scale, ob, dK + head_off, k0w, N, lane);
   store_transposed<T, D, C::OSTR>(dv, 1.0f, ob, dV + head_off, k0w, N, lane);
+  }  // rep
 }
 
 // ---------------------------------------------------------------------------------------
@@ -445,15 +455,22 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, c32 = lane & 31;
 
+  const int items = causal_items<CAUSAL>(nkt);  // causal: key tiles (p, nkt-1-p) are paired
   const int logical = xcd_contiguous(blockIdx.x, gridDim.x);
-  const int head = logical / nkt;
-  const int kt = logical - head * nkt;
+  const int head = logical / items;
+  const int item = logical - head * items;
 
   const size_t head_off = (size_t)head * N * D;
   const float* LSEh = LSE + (size_t)head * N;
   const float* Dh = Dws + (size_t)head * N;
   const BufView qview(Q + head_off, (uint32_t)N * D * 2), doview(dO + head_off, (uint32_t)N * D * 2);
 
+  for (int rep = 0; rep < (CAUSAL ? 2 : 1); ++rep) {
+  const int kt = CAUSAL ? (rep == 0 ? item : nkt - 1 - item) : item;  // the long tile first
+  if (CAUSAL && rep == 1) {
+    if (kt == item) break;  // odd tile count: the middle tile has no partner
+    __syncthreads();        // the first tile's epilogue is done with the LDS
+  }
   const int k0w = kt * C::BN + wave * 32;
   const int krow = k0w + c32;
   const int krow_c = krow < N ? krow : N - 1;
@@ -485,17 +502,19 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
     tile_b2r<D, C::BM>(doview, m * C::BM, tid, doreg);
     if (tid < 2 * C::BM) {
       const int row = m * C::BM + (tid & (C::BM - 1));
+      // raw values only: any arithmetic on them here would force a wait for the loads
       if (tid < C::BM)
-        statreg = row < N ? LSEh[row] * neg_inv_scale : -INFINITY;
+        statreg = row < N ? LSEh[row] : INFINITY;
       else
-        statreg = row < N ? -Dh[row] : 0.f;
+        statreg = row < N ? Dh[row] : 0.f;
     }
   };
   auto store_stage = [&](int slot) {  // registers -> LDS slot
     SPARK_LDS char* sb = smem + slot * C::STAGE;
     tile_r2s_swz<D, C::BM>(sb, tid, qreg);
     tile_r2s_swz<D, C::BM>(sb + C::TILE, tid, doreg);
-    if (tid < 2 * C::BM) lds_write(smem + C::STAT0 + slot * C::STAT, tid * 4, statreg);
+    if (tid < 2 * C::BM)
+      lds_write(smem + C::STAT0 + slot * C::STAT, tid * 4, statreg * (tid < C::BM ? neg_inv_scale : -1.0f));
   };
 
   // score fragments of the step whose S / dP are being formed (row reads) ...
@@ -553,14 +572,15 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
     }
   };
 
-  // One element of P and dS from finished scores (a few VALU instructions: the unit that is
-  // interleaved between two MFMAs of the next step's score contraction).
-  float p[16], ds[16];
-  auto softmax_elem = [&](const f32x16& s, const f32x16& dp, int r, int q0s, bool mask) {
+  // One element of P and dS from finished scores: the unit of VALU work that is placed between
+  // MFMAs.  (A single wave issues roughly one non-MFMA instruction per 5-7 cycles, an MFMA
+  // occupies the matrix core for ~36, so about half a dozen such instructions fit per MFMA.)
+  auto softmax_elem = [&](const f32x16& s, const f32x16& dp, int r, int q0s, bool mask, float* p,
+                          float* ds) {
     float pe = __builtin_amdgcn_exp2f(s[r] * scale_log2);
     if (mask) pe = krow > q0s + 8 * (r / 4) + 4 * g + (r % 4) ? 0.f : pe;
-    p[r] = pe;
-    ds[r] = pe * dp[r];
+    p[r & 7] = pe;
+    ds[r & 7] = pe * dp[r];
   };
 
   // ---- prologue: stages s_begin and s_begin+1 resident, scores of the first step formed ----
@@ -587,21 +607,30 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
     if (gi + 2 < NG) load_agroup(gi + 2, 0);
     sched_fence();
   }
+  // P / dS operands of the current step: registers 0..7 (pfL, dsfL) are formed one region
+  // early, registers 8..15 (pfH, dsfH) while the next step's scores are on the matrix cores.
+  v8 pfL, dsfL;
+  {
+    float p[8], ds[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) softmax_elem(sX, dpX, r, s_begin * C::BM, CAUSAL, p, ds);
+    pfL = pack8<T>(p);
+    dsfL = pack8<T>(ds);
+  }
 
-  // One stage: steps (m, 0) and (m, 1).  On entry sX / dpX hold the scores of (m, 0), rowA
-  // points at stage m and trC at stage m; on exit sX / dpX hold the scores of (m+1, 0).
+  // One stage: steps (m, 0) and (m, 1).  On entry sX / dpX hold the scores of (m, 0) and
+  // pfL / dsfL their first half; rowA and trC point at stage m.  On exit the same holds for
+  // (m+1, 0).
   auto stage = [&](int m, int slot, bool mask) {
     if (m + 2 < ns) load_stage(m + 2);
     const int slot1 = slot == 2 ? 0 : slot + 1;
     const int slot2 = slot1 == 2 ? 0 : slot1 + 1;
 
-    // The two halves of a stage differ only in which score registers are produced / consumed
-    // and in where the next scores come from.
-    auto half = [&](f32x16& s_new, f32x16& dp_new, int sub_new, const f32x16& s_cur,
-                    const f32x16& dp_cur, int sub_cur) {
-      // ---- scores of the next step  ||  P, dS of the current step ----
-      // 16 units of {1 MFMA, 1 softmax element, a share of the LDS reads}; the fences keep the
-      // units apart so that VALU work sits between consecutive MFMAs.
+    // One step.  cur: scores complete, first half of P / dS packed.  new: the step after it.
+    auto step = [&](f32x16& s_new, f32x16& dp_new, int sub_new, int q0_new, const f32x16& s_cur,
+                    const f32x16& dp_cur, int sub_cur, int q0_cur) {
+      // ---- region 1: scores of the next step  ||  second half of P, dS of the current step ----
+      float p[8], ds[8];
       load_tgroup(0, sub_cur);
 #pragma unroll
       for (int i = 0; i < 4 * NG; ++i) {
@@ -612,27 +641,31 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
           dp_new = F::mfma(fa[gi & 1][2 * e + 1], vf[2 * gi + e], dp_new);
         if ((i & 3) == 3 && gi + 2 < NG) load_agroup(gi + 2, sub_new);
         if (i == 2 * NG) load_tgroup(1, sub_cur);
-        softmax_elem(s_cur, dp_cur, i, m * C::BM + sub_cur * 32, mask);
+        if (i & 1) softmax_elem(s_cur, dp_cur, 8 + i / 2, q0_cur, mask, p, ds);
         sched_fence();
       }
-      v8 pf[2], dsf[2];
-#pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-        pf[kk] = pack8<T>(&p[kk * 8]);
-        dsf[kk] = pack8<T>(&ds[kk * 8]);
-      }
-      // ---- dV, dK of the current step; operands of the step after next are requested ----
+      const v8 pfH = pack8<T>(p), dsfH = pack8<T>(ds);
+      sched_fence();
+      // ---- region 2: dV, dK of the current step  ||  first half of P, dS of the next step ----
 #pragma unroll
       for (int tg = 0; tg < NTG; ++tg) {
         const int kk = tg / (DT / 2), dt0 = 2 * (tg % (DT / 2));
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
-          dv[dt0 + e] = F::mfma(ft[tg & 1][2 * e], pf[kk], dv[dt0 + e]);
-          dk[dt0 + e] = F::mfma(ft[tg & 1][2 * e + 1], dsf[kk], dk[dt0 + e]);
+          dv[dt0 + e] = F::mfma(ft[tg & 1][2 * e], kk ? pfH : pfL, dv[dt0 + e]);
+          dk[dt0 + e] = F::mfma(ft[tg & 1][2 * e + 1], kk ? dsfH : dsfL, dk[dt0 + e]);
+          softmax_elem(s_new, dp_new, (8 / NTG) * tg + e, q0_new, mask, p, ds);
+          if (8 / NTG > 2) softmax_elem(s_new, dp_new, (8 / NTG) * tg + 2 + e, q0_new, mask, p, ds);
+          sched_fence();
         }
         if (tg + 2 < NTG) load_tgroup(tg + 2, sub_cur);
         sched_fence();
       }
+      pfL = pack8<T>(p);
+      dsfL = pack8<T>(ds);
+      // materialise here: otherwise this arithmetic sinks to its use in the next step and
+      // runs there with no MFMA to hide it
+      asm volatile("" : "+v"(pfL), "+v"(dsfL));
     };
 
     // (m, 1) scores  ||  (m, 0) softmax; then (m, 0) dV / dK
@@ -640,14 +673,14 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
     load_agroup(0, 1);
     load_agroup(1, 1);
     sched_fence();
-    half(sY, dpY, 1, sX, dpX, 0);
+    step(sY, dpY, 1, m * C::BM + 32, sX, dpX, 0, m * C::BM);
     // (m+1, 0) scores  ||  (m, 1) softmax; then (m, 1) dV / dK
     point_A(slot1);
     init_scores(sX, dpX, 0);
     load_agroup(0, 0);
     load_agroup(1, 0);
     sched_fence();
-    half(sX, dpX, 0, sY, dpY, 1);
+    step(sX, dpX, 0, (m + 1) * C::BM, sY, dpY, 1, m * C::BM + 32);
 
     // stage m+2 goes into the slot that stage m-1 used; everybody left that slot before the
     // previous barrier
@@ -672,6 +705,7 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
   SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
   store_transposed<T, D, C::OSTR>(dk, scale, ob, dK + head_off, k0w, N, lane);
   store_transposed<T, D, C::OSTR>(dv, 1.0f, ob, dV + head_off, k0w, N, lane);
+  }  // rep
 }
 
 // ---------------------------------------------------------------------------------------
@@ -707,14 +741,20 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, c32 = lane & 31;
 
+  const int items = causal_items<CAUSAL>(nqt);  // causal: query tiles (nqt-1-p, p) are paired
   const int logical = xcd_contiguous(blockIdx.x, gridDim.x);
-  const int head = logical / nqt;
-  const int rank = logical - head * nqt;
-  const int qt = CAUSAL ? nqt - 1 - rank : rank;
+  const int head = logical / items;
+  const int item = logical - head * items;
 
   const size_t head_off = (size_t)head * N * D;
   const BufView kview(K + head_off, (uint32_t)N * D * 2), vview(V + head_off, (uint32_t)N * D * 2);
 
+  for (int rep = 0; rep < (CAUSAL ? 2 : 1); ++rep) {
+  const int qt = CAUSAL ? (rep == 0 ? nqt - 1 - item : item) : item;  // the long tile first
+  if (CAUSAL && rep == 1) {
+    if (qt == nqt - 1 - item) break;  // odd tile count: the middle tile has no partner
+    __syncthreads();                  // the first tile's epilogue is done with the LDS
+  }
   const int q0 = qt * C::BM + wave * 32;
   const int qrow = q0 + c32;
   const int qrow_c = qrow < N ? qrow : N - 1;
@@ -852,6 +892,7 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
 
   SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
   store_transposed<T, D, C::OSTR>(dq, scale, ob, dQ + head_off, q0, N, lane);
+  }  // rep
 }
 
 }  // namespace spark

@@ -48,6 +48,13 @@ static __device__ __forceinline__ int xcd_contiguous(int id, int total) {
   return base + slot;
 }
 
+// Work items per head for a kernel that walks `tiles` tiles: causal kernels pair tile p with
+// tile tiles-1-p.
+template <bool CAUSAL>
+static __host__ __device__ __forceinline__ int causal_items(int tiles) {
+  return CAUSAL ? (tiles + 1) / 2 : tiles;
+}
+
 template <typename T, int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
@@ -67,15 +74,25 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, c32 = lane & 31, i16 = lane & 15;
 
+  // Work items.  Non-causal: one query tile per workgroup.  Causal: a workgroup takes the pair
+  // of tiles (nqt-1-p, p), whose loop lengths add up to the same total for every p, so that
+  // all workgroups carry equal work and the launch has no tail of long tiles.
+  const int items = causal_items<CAUSAL>(nqt);
   const int logical = xcd_contiguous(blockIdx.x, gridDim.x);
-  const int head = logical / nqt;
-  const int rank = logical - head * nqt;
-  const int qt = CAUSAL ? nqt - 1 - rank : rank;  // causal: longest tiles first
+  const int head = logical / items;
+  const int item = logical - head * items;
 
   const size_t head_off = (size_t)head * N * D;
   const T* Qh = Q + head_off;
   const T* Kh = K + head_off;
   const T* Vh = V + head_off;
+
+  for (int rep = 0; rep < (CAUSAL ? 2 : 1); ++rep) {
+  const int qt = CAUSAL ? (rep == 0 ? nqt - 1 - item : item) : item;
+  if (CAUSAL && rep == 1) {
+    if (qt == nqt - 1 - item) break;  // odd tile count: the middle tile has no partner
+    __syncthreads();                  // the first tile's epilogue is done with the LDS
+  }
 
   const int q0 = qt * C::BM + wave * 32;  // first query row of this wave
   const int qrow = q0 + c32;              // this lane's query row
@@ -271,6 +288,7 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
   }
   if (g == 0 && qrow < N)
     LSE[(size_t)head * N + qrow] = (m_run + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f;
+  }  // rep
 }
 
 }  // namespace spark

@@ -43,7 +43,7 @@ int launch_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
   if (attr != SPARK_OK) return attr;
   const int nqt = (N + C::BM - 1) / C::BM;
   const float scale_log2 = scale * 1.4426950408889634f;
-  hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * nqt)), dim3(256), C::SMEM, st,
+  hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nqt))), dim3(256), C::SMEM, st,
                      static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
                      static_cast<T*>(O), LSE, N, nqt, scale_log2);
   return hipGetLastError() == hipSuccess ? SPARK_OK : SPARK_ERR_LAUNCH;
@@ -78,7 +78,7 @@ int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const
     static const int attr = set_smem(kernel, C::SMEM);
     if (attr != SPARK_OK) return attr;
     const int nkt = (N + C::BN - 1) / C::BN;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * nkt)), dim3(256), C::SMEM, st, q, k, v, dout,
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nkt))), dim3(256), C::SMEM, st, q, k, v, dout,
                        LSE, Dws, static_cast<T*>(dK), static_cast<T*>(dV), N, nkt, scale,
                        scale_log2);
     if (hipGetLastError() != hipSuccess || !mark(2)) return SPARK_ERR_LAUNCH;
@@ -88,7 +88,7 @@ int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const
     static const int attr = set_smem(kernel, C::SMEM);
     if (attr != SPARK_OK) return attr;
     const int nkt = (N + C::BN - 1) / C::BN;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * nkt)), dim3(256), C::SMEM, st, q, k, v, dout,
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nkt))), dim3(256), C::SMEM, st, q, k, v, dout,
                        LSE, Dws, static_cast<T*>(dK), static_cast<T*>(dV), N, nkt, scale,
                        scale_log2);
     if (hipGetLastError() != hipSuccess || !mark(2)) return SPARK_ERR_LAUNCH;
@@ -99,7 +99,7 @@ int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const
     static const int attr = set_smem(kernel, C::SMEM);
     if (attr != SPARK_OK) return attr;
     const int nqt = (N + C::BM - 1) / C::BM;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * nqt)), dim3(256), C::SMEM, st, q, k, v, dout,
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nqt))), dim3(256), C::SMEM, st, q, k, v, dout,
                        LSE, Dws, static_cast<T*>(dQ), N, nqt, scale, scale_log2);
     if (hipGetLastError() != hipSuccess || !mark(3)) return SPARK_ERR_LAUNCH;
   }
