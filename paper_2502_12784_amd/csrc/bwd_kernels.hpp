@@ -26,13 +26,16 @@
 namespace spark {
 
 // ---------------------------------------------------------------------------------------
-// D = rowsum(dO o O).  One thread per 16-byte chunk of a row; D/8 neighbouring lanes share a
-// row and reduce with shuffles.  Pure streaming: reads two tensors, writes BH*N floats.
+// D = rowsum(dO o O), and LSE * log2(e) next to it.  One thread per 16-byte chunk of a row;
+// D/8 neighbouring lanes share a row and reduce with shuffles.  Pure streaming: reads two
+// tensors, writes 2*BH*N floats.
 // ---------------------------------------------------------------------------------------
 template <typename T, int D>
 __global__ __launch_bounds__(256) void mha_bwd_dot_kernel(const T* __restrict__ O,
                                                          const T* __restrict__ dO,
-                                                         float* __restrict__ Dout, int64_t rows) {
+                                                         const float* __restrict__ LSE,
+                                                         float* __restrict__ Dout,
+                                                         float* __restrict__ LSE2out, int64_t rows) {
   using v8 = typename Frag<T>::v8;
   constexpr int CPR = D / 8;
   const int64_t chunk = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -46,7 +49,10 @@ __global__ __launch_bounds__(256) void mha_bwd_dot_kernel(const T* __restrict__ 
   }
 #pragma unroll
   for (int off = CPR / 2; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
-  if (row < rows && (threadIdx.x % CPR) == 0) Dout[row] = acc;
+  if (row < rows && (threadIdx.x % CPR) == 0) {
+    Dout[row] = acc;
+    LSE2out[row] = LSE[row] * 1.4426950408889634f;  // the backward kernels exponentiate in base 2
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -414,40 +420,59 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_kernel(
 //
 // At d = 128 the accumulators (dK^T, dV^T: 128 registers) and the resident K / V fragments
 // (64) leave room for one wave per SIMD only, so nothing but the wave itself can hide its
-// softmax arithmetic and LDS latency.  The loop is therefore skewed by one 32-query step:
-// while the VALU turns the scores of step i into P and dS, the matrix cores already compute
-// the scores of step i+1; the dV / dK MFMAs of step i follow.  Because step i+1 may lie in the
-// next 64-query stage, stages live in a ring of three LDS slots (stage m+1 is resident while
-// stage m is processed, stage m+2 is in flight in registers).  No step is skipped: blocks above
-// the causal diagonal are masked to zero (first two stages of a workgroup only), rows past the
-// end of the sequence have P = 0 through their statistics.
+// softmax arithmetic and LDS latency.  A wave issues in order, and an MFMA occupies the matrix
+// core for ~34 cycles while the wave can issue about half a dozen other instructions; so the
+// loop is skewed by one 32-query step and written as units of {one MFMA, a few VALU / LDS
+// instructions}:
+//   region 1:  scores of step i+1 (MFMA)   ||  second half of P, dS of step i      (VALU)
+//   region 2:  dV, dK of step i   (MFMA)   ||  first half of P, dS of step i+1     (VALU)
+// Because step i+1 may lie in the next 64-query stage, stages live in a ring of three LDS
+// slots: stage m+1 is resident while stage m is processed, and stage m+2 is being written by
+// direct global->LDS loads (no staging registers, no LDS store instructions).  No step is
+// skipped: blocks above the causal diagonal are masked to zero (first two stages of a workgroup
+// only); rows past the end of the sequence read as zeros (Q = dO = 0), so they add nothing.
 // ---------------------------------------------------------------------------------------
 template <int D> struct BwdKvPipeCfg {
   static constexpr int BN = 128, BM = 64, SLOTS = 3;
   static constexpr int ROWB = D * 2;
   static constexpr int TILE = BM * ROWB;
   static constexpr int STAGE = 2 * TILE;
-  static constexpr int STAT = 2 * BM * 4;
+  static constexpr int STAT = 2 * BM * 4;  // LSE*log2(e) and D of the stage's rows
   static constexpr int OSTR = D * 2 + 16;
   static constexpr int STAT0 = SLOTS * STAGE;  // LDS = [slot 0..2 | stat 0..2]
   static constexpr int SMEM = SLOTS * STAGE + SLOTS * STAT;
   static_assert(4 * 32 * OSTR <= SLOTS * STAGE, "epilogue staging must fit");
 };
 
-#define SPARK_SGB_MFMA(n) __builtin_amdgcn_sched_group_barrier(0x008, n, 0)
-#define SPARK_SGB_VALU(n) __builtin_amdgcn_sched_group_barrier(0x002, n, 0)
-#define SPARK_SGB_DSR(n) __builtin_amdgcn_sched_group_barrier(0x100, n, 0)
+// Direct global->LDS copy of a swizzled ROWS x D tile: wave w of the 4 waves fills the 1 KB
+// blocks w, w+4, ... of the tile; lane l writes bytes [16 l, 16 l + 16) of its block, so it
+// fetches the logical chunk that the swizzle places there.  `lane_src` is that per-lane source
+// offset for block `wave` (the later blocks are a multiple of 16 rows further on, where the
+// swizzle repeats).  Rows past the end of the matrix arrive as zeros.
+template <int D>
+static __device__ __forceinline__ uint32_t dma_lane_src(int wave, int lane) {
+  const int byte = wave * 1024 + lane * 16;
+  const int row = byte / (2 * D), pc = (byte % (2 * D)) >> 4;
+  return (uint32_t)(row * (2 * D) + ((pc ^ swz<D>(row)) << 4));
+}
+template <int D, int ROWS>
+static __device__ __forceinline__ void tile_dma(const BufView& view, int r0, SPARK_LDS char* dst,
+                                                int wave, uint32_t lane_src) {
+  static_assert((4 * 1024 / (2 * D)) % 16 == 0, "blocks of one wave must be 16 rows apart");
+#pragma unroll
+  for (int i = 0; i < ROWS * 2 * D / 4096; ++i)
+    view.load16_to_lds(dst + (i * 4 + wave) * 1024, lane_src, (uint32_t)r0 * (2 * D) + i * 4096);
+}
 
 template <typename T, int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
-    const T* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Dws,
-    T* __restrict__ dK, T* __restrict__ dV, int N, int nkt, float scale, float scale_log2) {
+    const T* __restrict__ dO, const float* __restrict__ LSE2, const float* __restrict__ Dws,
+    T* __restrict__ dK, T* __restrict__ dV, int N, int nkt, float scale) {
   using F = Frag<T>;
   using v8 = typename F::v8;
   using C = BwdKvPipeCfg<D>;
   constexpr int KS = D / 16, DT = D / 32;
-  constexpr int NLD = C::BM * (D / 8) / 256;
 
   extern __shared__ __attribute__((aligned(16))) char smem_generic[];
   SPARK_LDS char* smem = (SPARK_LDS char*)smem_generic;
@@ -461,9 +486,10 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
   const int item = logical - head * items;
 
   const size_t head_off = (size_t)head * N * D;
-  const float* LSEh = LSE + (size_t)head * N;
-  const float* Dh = Dws + (size_t)head * N;
   const BufView qview(Q + head_off, (uint32_t)N * D * 2), doview(dO + head_off, (uint32_t)N * D * 2);
+  const BufView lview(LSE2 + (size_t)head * N, (uint32_t)N * 4), dview(Dws + (size_t)head * N, (uint32_t)N * 4);
+  const uint32_t lane_src = dma_lane_src<D>(wave, lane);
+  const float scale_log2 = scale * 1.4426950408889634f;
 
   for (int rep = 0; rep < (CAUSAL ? 2 : 1); ++rep) {
   const int kt = CAUSAL ? (rep == 0 ? item : nkt - 1 - item) : item;  // the long tile first
@@ -491,33 +517,21 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
   const int ns = (N + C::BM - 1) / C::BM;
   const int s_begin = CAUSAL ? (kt * C::BN) / C::BM : 0;
 
-  const SwzLane<D> lane_off(lane);       // offsets inside slot 0
+  const SwzLane<D> lane_off(lane);  // offsets inside slot 0
   const int lane_stat = C::STAT0 + 16 * g;
-  const float neg_inv_scale = -1.0f / scale;
 
-  u32x4 qreg[NLD], doreg[NLD];
-  float statreg = 0.f;
-  auto load_stage = [&](int m) {  // global -> registers
-    tile_b2r<D, C::BM>(qview, m * C::BM, tid, qreg);
-    tile_b2r<D, C::BM>(doview, m * C::BM, tid, doreg);
-    if (tid < 2 * C::BM) {
-      const int row = m * C::BM + (tid & (C::BM - 1));
-      // raw values only: any arithmetic on them here would force a wait for the loads
-      if (tid < C::BM)
-        statreg = row < N ? LSEh[row] : INFINITY;
-      else
-        statreg = row < N ? Dh[row] : 0.f;
-    }
-  };
-  auto store_stage = [&](int slot) {  // registers -> LDS slot
+  // global -> LDS slot, asynchronously (completion is awaited with wait_vmem_all + barrier)
+  auto fetch_stage = [&](int m, int slot) {
     SPARK_LDS char* sb = smem + slot * C::STAGE;
-    tile_r2s_swz<D, C::BM>(sb, tid, qreg);
-    tile_r2s_swz<D, C::BM>(sb + C::TILE, tid, doreg);
-    if (tid < 2 * C::BM)
-      lds_write(smem + C::STAT0 + slot * C::STAT, tid * 4, statreg * (tid < C::BM ? neg_inv_scale : -1.0f));
+    tile_dma<D, C::BM>(qview, m * C::BM, sb, wave, lane_src);
+    tile_dma<D, C::BM>(doview, m * C::BM, sb + C::TILE, wave, lane_src);
+    // 64 floats of LSE*log2(e) (wave 0) and of D (wave 1): 4 bytes per lane
+    SPARK_LDS char* st = smem + C::STAT0 + slot * C::STAT;
+    if (wave == 0) lview.load4_to_lds(st, lane * 4, (uint32_t)m * C::BM * 4);
+    if (wave == 1) dview.load4_to_lds(st + C::BM * 4, lane * 4, (uint32_t)m * C::BM * 4);
   };
 
-  // score fragments of the step whose S / dP are being formed (row reads) ...
+  // LDS read offsets of the step whose scores are being formed (row reads, statistics) ...
   int rowA[KS], statA;
   // ... and of the step whose dV / dK are being accumulated (transposing reads)
   int trC[2][DT];
@@ -533,7 +547,6 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
       for (int dt = 0; dt < DT; ++dt) trC[h][dt] = lane_off.tr[h][dt] + slot * C::STAGE;
   };
 
-  // S - LSE/scale and dP - D of one 32-query step (sub = 0/1 inside the stage rowA points to)
   v8 fa[2][4];
   auto load_agroup = [&](int gi, int sub) {
 #pragma unroll
@@ -542,21 +555,14 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
       fa[gi & 1][2 * e + 1] = lds_read16<v8>(smem + C::TILE, rowA[2 * gi + e] + sub * 32 * C::ROWB);
     }
   };
-  auto init_scores = [&](f32x16& s, f32x16& dp, int sub) {
+  // statistics of 8 of the 16 query rows a lane holds (half = 0: registers 0..7, 1: 8..15) of the
+  // step rowA / statA point at
+  auto load_stats = [&](f32x4 (&l)[2], f32x4 (&d)[2], int sub, int half) {
 #pragma unroll
-    for (int r4 = 0; r4 < 4; ++r4) {
-      const int o = statA + (sub * 32 + 8 * r4) * 4;
-      const f32x4 l4 = lds_read16<f32x4>(smem, o);
-      const f32x4 d4 = lds_read16<f32x4>(smem, o + C::BM * 4);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) { s[r4 * 4 + e] = l4[e]; dp[r4 * 4 + e] = d4[e]; }
-    }
-  };
-  auto mfma_agroup = [&](f32x16& s, f32x16& dp, int gi) {
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-      s = F::mfma(fa[gi & 1][2 * e], kf[2 * gi + e], s);
-      dp = F::mfma(fa[gi & 1][2 * e + 1], vf[2 * gi + e], dp);
+    for (int x = 0; x < 2; ++x) {
+      const int o = statA + (sub * 32 + 8 * (2 * half + x)) * 4;
+      l[x] = lds_read16<f32x4>(smem, o);
+      d[x] = lds_read16<f32x4>(smem, o + C::BM * 4);
     }
   };
   constexpr int NG = KS / 2;
@@ -573,64 +579,77 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
   };
 
   // One element of P and dS from finished scores: the unit of VALU work that is placed between
-  // MFMAs.  (A single wave issues roughly one non-MFMA instruction per 5-7 cycles, an MFMA
-  // occupies the matrix core for ~36, so about half a dozen such instructions fit per MFMA.)
-  auto softmax_elem = [&](const f32x16& s, const f32x16& dp, int r, int q0s, bool mask, float* p,
-                          float* ds) {
-    float pe = __builtin_amdgcn_exp2f(s[r] * scale_log2);
+  // MFMAs.  r8 = register index within the half (0..7).
+  auto softmax_elem = [&](const f32x16& s, const f32x16& dp, int half, int r8, const f32x4 (&l)[2],
+                          const f32x4 (&d)[2], int q0s, bool mask, float* p, float* ds) {
+    const int r = 8 * half + r8;
+    float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, -l[r8 >> 2][r8 & 3]));
     if (mask) pe = krow > q0s + 8 * (r / 4) + 4 * g + (r % 4) ? 0.f : pe;
-    p[r & 7] = pe;
-    ds[r & 7] = pe * dp[r];
+    p[r8] = pe;
+    ds[r8] = pe * (dp[r] - d[r8 >> 2][r8 & 3]);
   };
 
   // ---- prologue: stages s_begin and s_begin+1 resident, scores of the first step formed ----
-  load_stage(s_begin);
+  fetch_stage(s_begin, 0);
+  if (s_begin + 1 < ns) fetch_stage(s_begin + 1, 1);
   wait_vmem_all();
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(kf[ks]), "+v"(vf[ks]));
-  store_stage(0);
-  if (s_begin + 1 < ns) {
-    load_stage(s_begin + 1);
-    store_stage(1);
-  }
   __syncthreads();
 
   point_A(0);
   point_C(0);
   f32x16 sX, dpX, sY, dpY;
-  init_scores(sX, dpX, 0);
+  f32x4 lL[2], dL[2], lH[2], dH[2];  // statistics: first half of the next step / second half of the current
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { sX[r] = 0.f; dpX[r] = 0.f; }
   load_agroup(0, 0);
   load_agroup(1, 0);
+  load_stats(lL, dL, 0, 0);
 #pragma unroll
   for (int gi = 0; gi < NG; ++gi) {
-    mfma_agroup(sX, dpX, gi);
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      sX = F::mfma(fa[gi & 1][2 * e], kf[2 * gi + e], sX);
+      dpX = F::mfma(fa[gi & 1][2 * e + 1], vf[2 * gi + e], dpX);
+    }
     if (gi + 2 < NG) load_agroup(gi + 2, 0);
     sched_fence();
   }
+  // The MFMAs deliver the scores in accumulation registers, which the VALU cannot use as
+  // operands, and a copy out of them stalls while any MFMA is executing (measured: reading them
+  // element by element between MFMAs serialises the two pipes completely).  So each finished
+  // score tile is copied to VALU registers in one burst, right after the region that formed it,
+  // and all softmax arithmetic works on the copies sV / dpV.
+  f32x16 sV = sX, dpV = dpX;
+  asm volatile("" : "+v"(sV), "+v"(dpV));
   // P / dS operands of the current step: registers 0..7 (pfL, dsfL) are formed one region
   // early, registers 8..15 (pfH, dsfH) while the next step's scores are on the matrix cores.
   v8 pfL, dsfL;
   {
     float p[8], ds[8];
 #pragma unroll
-    for (int r = 0; r < 8; ++r) softmax_elem(sX, dpX, r, s_begin * C::BM, CAUSAL, p, ds);
+    for (int r = 0; r < 8; ++r) softmax_elem(sV, dpV, 0, r, lL, dL, s_begin * C::BM, CAUSAL, p, ds);
     pfL = pack8<T>(p);
     dsfL = pack8<T>(ds);
   }
+  load_stats(lH, dH, 0, 1);
 
-  // One stage: steps (m, 0) and (m, 1).  On entry sX / dpX hold the scores of (m, 0) and
-  // pfL / dsfL their first half; rowA and trC point at stage m.  On exit the same holds for
-  // (m+1, 0).
+  // One stage: steps (m, 0) and (m, 1).  On entry sX / dpX hold the scores of (m, 0), pfL / dsfL
+  // their first half and lH / dH the statistics of their second half; rowA and trC point at
+  // stage m.  On exit the same holds for (m+1, 0).
   auto stage = [&](int m, int slot, bool mask) {
-    if (m + 2 < ns) load_stage(m + 2);
     const int slot1 = slot == 2 ? 0 : slot + 1;
     const int slot2 = slot1 == 2 ? 0 : slot1 + 1;
+    // stage m+2 goes into the slot that stage m-1 used; everybody left it before the last barrier
+    if (m + 2 < ns) fetch_stage(m + 2, slot2);
 
-    // One step.  cur: scores complete, first half of P / dS packed.  new: the step after it.
-    auto step = [&](f32x16& s_new, f32x16& dp_new, int sub_new, int q0_new, const f32x16& s_cur,
-                    const f32x16& dp_cur, int sub_cur, int q0_cur) {
+    // One step.  cur: scores complete, first half of P / dS packed.  new: the step after it
+    // (sub_new inside the stage rowA / statA point at).
+    auto step = [&](f32x16& s_new, f32x16& dp_new, int sub_new, int q0_new, int sub_cur, int q0_cur) {
       // ---- region 1: scores of the next step  ||  second half of P, dS of the current step ----
       float p[8], ds[8];
+      load_stats(lL, dL, sub_new, 0);
       load_tgroup(0, sub_cur);
 #pragma unroll
       for (int i = 0; i < 4 * NG; ++i) {
@@ -641,10 +660,15 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
           dp_new = F::mfma(fa[gi & 1][2 * e + 1], vf[2 * gi + e], dp_new);
         if ((i & 3) == 3 && gi + 2 < NG) load_agroup(gi + 2, sub_new);
         if (i == 2 * NG) load_tgroup(1, sub_cur);
-        if (i & 1) softmax_elem(s_cur, dp_cur, 8 + i / 2, q0_cur, mask, p, ds);
+        if (i & 1) softmax_elem(sV, dpV, 1, i / 2, lH, dH, q0_cur, mask, p, ds);
         sched_fence();
       }
       const v8 pfH = pack8<T>(p), dsfH = pack8<T>(ds);
+      load_stats(lH, dH, sub_new, 1);
+      sched_fence();
+      sV = s_new;  // burst copy of the scores just formed (see above)
+      dpV = dp_new;
+      asm volatile("" : "+v"(sV), "+v"(dpV));
       sched_fence();
       // ---- region 2: dV, dK of the current step  ||  first half of P, dS of the next step ----
 #pragma unroll
@@ -654,8 +678,8 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
         for (int e = 0; e < 2; ++e) {
           dv[dt0 + e] = F::mfma(ft[tg & 1][2 * e], kk ? pfH : pfL, dv[dt0 + e]);
           dk[dt0 + e] = F::mfma(ft[tg & 1][2 * e + 1], kk ? dsfH : dsfL, dk[dt0 + e]);
-          softmax_elem(s_new, dp_new, (8 / NTG) * tg + e, q0_new, mask, p, ds);
-          if (8 / NTG > 2) softmax_elem(s_new, dp_new, (8 / NTG) * tg + 2 + e, q0_new, mask, p, ds);
+          softmax_elem(sV, dpV, 0, (8 / NTG) * tg + e, lL, dL, q0_new, mask, p, ds);
+          if (8 / NTG > 2) softmax_elem(sV, dpV, 0, (8 / NTG) * tg + 2 + e, lL, dL, q0_new, mask, p, ds);
           sched_fence();
         }
         if (tg + 2 < NTG) load_tgroup(tg + 2, sub_cur);
@@ -669,23 +693,23 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
     };
 
     // (m, 1) scores  ||  (m, 0) softmax; then (m, 0) dV / dK
-    init_scores(sY, dpY, 1);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { sY[r] = 0.f; dpY[r] = 0.f; }
     load_agroup(0, 1);
     load_agroup(1, 1);
     sched_fence();
-    step(sY, dpY, 1, m * C::BM + 32, sX, dpX, 0, m * C::BM);
+    step(sY, dpY, 1, m * C::BM + 32, 0, m * C::BM);
     // (m+1, 0) scores  ||  (m, 1) softmax; then (m, 1) dV / dK
     point_A(slot1);
-    init_scores(sX, dpX, 0);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { sX[r] = 0.f; dpX[r] = 0.f; }
     load_agroup(0, 0);
     load_agroup(1, 0);
     sched_fence();
-    step(sX, dpX, 0, (m + 1) * C::BM, sY, dpY, 1, m * C::BM + 32);
+    step(sX, dpX, 0, (m + 1) * C::BM, 1, m * C::BM + 32);
 
-    // stage m+2 goes into the slot that stage m-1 used; everybody left that slot before the
-    // previous barrier
-    if (m + 2 < ns) store_stage(slot2);
     point_C(slot1);
+    wait_vmem_all();  // stage m+2 has landed (it was requested a whole stage ago)
     __syncthreads();
   };
 

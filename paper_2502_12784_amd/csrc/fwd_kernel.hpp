@@ -157,35 +157,28 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
       SPARK_LDS const char* kb = smem + buf * C::STAGE;
       SPARK_LDS const char* vb = kb + C::KBYTES;
 
-      // S^T tile: 64 keys x 32 queries.  K fragments are read two k-steps (4 reads) ahead of
-      // the MFMAs that consume them; the fences pin that order against the scheduler, which
-      // would otherwise sink every read next to its use and serialise read -> wait -> MFMA.
+      // The 64-key tile is processed as two 32-key halves, each its own online-softmax step,
+      // so that the VALU work of one half sits between the MFMAs of the other:
+      //   S_0                   (MFMA)
+      //   S_1       ||  softmax of half 0   (an MFMA, then a few VALU instructions, ...)
+      //   O += P_0 V_0  ||  softmax of half 1
+      //   O += P_1 V_1
+      // A wave issues in order, so the VALU instructions must be placed between the MFMAs in
+      // program order; the fences keep the scheduler from regrouping them.  K fragments are read
+      // 8 reads ahead, V^T fragments one 16-key step ahead.
       f32x16 s[2];
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[mt][r] = 0.f;
-      constexpr int NG = KS / 2;  // groups of 2 k-steps x 2 key blocks
+      constexpr int GPH = KS / 4;  // groups of 4 k-steps per half
       v8 kf[2][4];
-      auto load_kgroup = [&](int gi) {
+      auto load_kgroup = [&](int gi) {  // gi = half * GPH + group
+        const int half = gi / GPH, ks0 = 4 * (gi % GPH);
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          kf[gi & 1][e] = lds_read16<v8>(kb, ((e & 1) * 32 + c32) * C::KSTR + (2 * gi + (e >> 1)) * 32 + g * 16);
+          kf[gi & 1][e] = lds_read16<v8>(kb, (half * 32 + c32) * C::KSTR + (ks0 + e) * 32 + g * 16);
       };
-      load_kgroup(0);
-      load_kgroup(1);
-      sched_fence();
-#pragma unroll
-      for (int gi = 0; gi < NG; ++gi) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          s[e & 1] = F::mfma(kf[gi & 1][e], qf[2 * gi + (e >> 1)], s[e & 1]);
-        if (gi + 2 < NG) load_kgroup(gi + 2);
-        sched_fence();
-      }
-
-      // V^T fragments of the first two 16-key steps are requested now, so that they arrive
-      // while the softmax arithmetic runs.
       v8 vf[2][DT];
       auto load_vgroup = [&](int kk) {
         const int row0 = 16 * kk + 4 * g + (i16 >> 2);
@@ -197,66 +190,123 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
           vf[kk & 1][dt] = join4<v8, v4>(lo, hi);
         }
       };
-      load_vgroup(0);
-      load_vgroup(1);
-      sched_fence();
-
-      float t[32];
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) t[mt * 16 + r] = s[mt][r];
 
       const bool need_mask = (CAUSAL && k0 + C::BN - 1 > q0) || (k0 + C::BN > N);
-      if (need_mask) {
+      float t[32];
+      // raw scores of one half -> t, masked; returns the scaled row maximum of the half
+      auto half_max = [&](int h) {
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+        for (int r = 0; r < 16; ++r) t[h * 16 + r] = s[h][r];
+        if (need_mask) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const int key = k0 + mt * 32 + 8 * (r / 4) + 4 * g + (r % 4);
+            const int key = k0 + h * 32 + 8 * (r / 4) + 4 * g + (r % 4);
             const bool ok = key < N && (!CAUSAL || key <= qrow);
-            if (!ok) t[mt * 16 + r] = -INFINITY;
+            if (!ok) t[h * 16 + r] = -INFINITY;
           }
-      }
-
-      // Row max of the raw scores (scale > 0, so it commutes with the scaling).
-      float mx = t[0];
+        }
+        float mx = t[h * 16];
 #pragma unroll
-      for (int i = 1; i < 32; ++i) mx = fmaxf(mx, t[i]);
-      mx = half_pair_max(mx) * scale_log2;
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, t[h * 16 + r]);
+        return half_pair_max(mx) * scale_log2;  // scale > 0 commutes with the maximum
+      };
+      float rs = 0.f;
+      auto exp_elem = [&](int i) {
+        t[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(t[i], scale_log2, -m_run));
+        rs += t[i];
+      };
+
+      // ---- S_0 ----
+      load_kgroup(0);
+      load_kgroup(1);
+      sched_fence();
+#pragma unroll
+      for (int gi = 0; gi < GPH; ++gi) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s[0] = F::mfma(kf[gi & 1][e], qf[4 * gi + e], s[0]);
+        if (gi + 2 < 2 * GPH) load_kgroup(gi + 2);
+        sched_fence();
+      }
+      load_vgroup(0);
+      sched_fence();
 
       // Online softmax (Eq. 3) with a lazy reference point: m_run is only moved, and the
       // accumulators only rescaled by exp(m_pre - m_cur), when some row's maximum grew by more
       // than 2^8.  Until then P is formed against the old reference and stays <= 256, which fp32
       // sums and the 16-bit MFMA operand hold without loss; the final O = acc / l and
       // LSE = m + log l do not depend on which reference was used.
-      if (__any(mx > m_run + 8.0f)) {
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
-        l_run *= alpha;
+      {
+        const float mx = half_max(0);
+        if (__any(mx > m_run + 8.0f)) {
+          const float m_new = fmaxf(m_run, mx);
+          const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+          m_run = m_new;
+          l_run *= alpha;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+          for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+            for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+        }
       }
-
-      float rs = 0.f;
+      // ---- S_1  ||  exponentials of half 0 ----
+      constexpr int EPU = 16 / KS;  // elements per MFMA
 #pragma unroll
-      for (int i = 0; i < 32; ++i) {
-        t[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(t[i], scale_log2, -m_run));
-        rs += t[i];
+      for (int gi = GPH; gi < 2 * GPH; ++gi) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          s[1] = F::mfma(kf[gi & 1][e], qf[4 * (gi - GPH) + e], s[1]);
+#pragma unroll
+          for (int x = 0; x < EPU; ++x) exp_elem(((gi - GPH) * 4 + e) * EPU + x);
+          sched_fence();
+        }
+        if (gi + 2 < 2 * GPH) load_kgroup(gi + 2);
+        if (gi == GPH) load_vgroup(1);
+        sched_fence();
+      }
+      // ---- boundary: reference check of half 1 (rarely moves; then P_0 is rescaled too) ----
+      {
+        const float mx = half_max(1);
+        if (__any(mx > m_run + 8.0f)) {
+          const float m_new = fmaxf(m_run, mx);
+          const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+          m_run = m_new;
+          l_run *= alpha;
+          rs *= alpha;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) t[i] *= alpha;
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+        }
+      }
+      v8 pf[4];
+      pf[0] = pack8<T>(&t[0]);
+      pf[1] = pack8<T>(&t[8]);
+      sched_fence();
+      // ---- O^T += V_0^T P_0^T  ||  exponentials of half 1 ----
+      constexpr int EPV = 16 / (2 * DT);  // elements per MFMA
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          o[dt] = F::mfma(vf[kk & 1][dt], pf[kk], o[dt]);
+#pragma unroll
+          for (int x = 0; x < EPV; ++x) exp_elem(16 + (kk * DT + dt) * EPV + x);
+          sched_fence();
+        }
+        load_vgroup(kk + 2);
+        sched_fence();
       }
       l_run += rs;
-
-      // O^T += V^T P^T, 16 keys per step, V^T fragments two steps ahead
+      pf[2] = pack8<T>(&t[16]);
+      pf[3] = pack8<T>(&t[24]);
       sched_fence();
+      // ---- O^T += V_1^T P_1^T ----
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const v8 pf = pack8<T>(&t[kk * 8]);
+      for (int kk = 2; kk < 4; ++kk) {
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) o[dt] = F::mfma(vf[kk & 1][dt], pf, o[dt]);
-        if (kk + 2 < 4) load_vgroup(kk + 2);
+        for (int dt = 0; dt < DT; ++dt) o[dt] = F::mfma(vf[kk & 1][dt], pf[kk], o[dt]);
         sched_fence();
       }
     }

@@ -106,10 +106,43 @@ static __device__ __forceinline__ float half_pair_sum(float x) {
 // main loops).  The matrix must be smaller than 4 GiB.
 struct BufView {
   __amdgpu_buffer_rsrc_t rsrc;
+  u32x4 desc;  // the same descriptor as four dwords (base, base_hi | stride 0, bytes, flags)
   __device__ __forceinline__ BufView(const void* base, uint32_t bytes)
-      : rsrc(__builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000)) {}
+      : rsrc(__builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000)) {
+    const uint64_t a = reinterpret_cast<uint64_t>(base);
+    desc[0] = (uint32_t)a;
+    desc[1] = (uint32_t)(a >> 32) & 0xffffu;
+    desc[2] = bytes;
+    desc[3] = 0x00020000u;
+  }
   __device__ __forceinline__ u32x4 load16(uint32_t lane_off, uint32_t tile_off) const {
     return __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane_off, tile_off, 0);
+  }
+  // Direct global->LDS load (no registers): lane l of the wave writes its 16 (or 4) bytes at
+  // LDS byte address dst + 16 l (4 l); dst must be wave-uniform.  Out-of-range lanes write
+  // zeros.  Completion is counted by vmcnt.
+  //
+  // Issued as inline assembly on purpose: for the builtin form the compiler cannot tell which
+  // LDS bytes the load writes and puts a full vmcnt(0) wait in front of every later LDS read,
+  // which would expose the whole global-memory latency.  The caller therefore owns the
+  // synchronisation: wait_vmem_all() followed by a workgroup barrier before anyone reads the
+  // destination.  (The compiler's own vmcnt waits stay correct: loads return in order, so
+  // extra outstanding loads can only make such a wait longer, never shorter.)  M0 is written
+  // without telling the compiler (it rejects M0 as a clobber); nothing else in these kernels
+  // uses M0: no other LDS-DMA, GWS or relative-index instruction is generated.
+  __device__ __forceinline__ void load16_to_lds(SPARK_LDS char* dst, uint32_t lane_off, uint32_t tile_off) const {
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(__builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst)), "v"(lane_off), "s"(desc),
+                   "s"(__builtin_amdgcn_readfirstlane(tile_off))
+                 : "memory");
+  }
+  __device__ __forceinline__ void load4_to_lds(SPARK_LDS char* dst, uint32_t lane_off, uint32_t tile_off) const {
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                 :
+                 : "s"(__builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst)), "v"(lane_off), "s"(desc),
+                   "s"(__builtin_amdgcn_readfirstlane(tile_off))
+                 : "memory");
   }
 };
 

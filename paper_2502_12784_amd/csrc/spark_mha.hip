@@ -59,6 +59,7 @@ int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const
   const T* o = static_cast<const T*>(O);
   const T* dout = static_cast<const T*>(dO);
   const float scale_log2 = scale * 1.4426950408889634f;
+  float* LSE2ws = Dws + (size_t)BH * N;  // second half of the workspace: LSE * log2(e)
   // optional profiling marks between the kernels (spark_mha_bwd_marked)
   auto mark = [&](int i) {
     return !ev || hipEventRecord(static_cast<hipEvent_t>(ev[i]), st) == hipSuccess;
@@ -69,7 +70,8 @@ int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const
     constexpr int ROWS_PER_BLOCK = 256 / (D / 8);
     const int64_t rows = (int64_t)BH * N;
     const unsigned grid = (unsigned)((rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK);
-    hipLaunchKernelGGL((mha_bwd_dot_kernel<T, D>), dim3(grid), dim3(256), 0, st, o, dout, Dws, rows);
+    hipLaunchKernelGGL((mha_bwd_dot_kernel<T, D>), dim3(grid), dim3(256), 0, st, o, dout, LSE, Dws,
+                       LSE2ws, rows);
     if (hipGetLastError() != hipSuccess || !mark(1)) return SPARK_ERR_LAUNCH;
   }
   if constexpr (D == 128) {  // dK, dV: one workgroup per tile of 128 keys, software-pipelined
@@ -79,8 +81,7 @@ int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const
     if (attr != SPARK_OK) return attr;
     const int nkt = (N + C::BN - 1) / C::BN;
     hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nkt))), dim3(256), C::SMEM, st, q, k, v, dout,
-                       LSE, Dws, static_cast<T*>(dK), static_cast<T*>(dV), N, nkt, scale,
-                       scale_log2);
+                       LSE2ws, Dws, static_cast<T*>(dK), static_cast<T*>(dV), N, nkt, scale);
     if (hipGetLastError() != hipSuccess || !mark(2)) return SPARK_ERR_LAUNCH;
   } else {  // dK, dV: one workgroup per tile of 128 keys, two workgroups per CU
     using C = BwdKvCfg<D>;
@@ -140,7 +141,7 @@ int spark_mha_fwd(const void* Q, const void* K, const void* V, void* O, float* L
 
 size_t spark_mha_bwd_workspace_bytes(int B, int H, int N, int d, spark_dtype_t dtype) {
   if (check_common(B, H, N, d, 1.0f, (int)dtype) != SPARK_OK) return 0;
-  return (size_t)B * H * N * sizeof(float);
+  return 2 * (size_t)B * H * N * sizeof(float);  // D and LSE*log2(e), fp32 [B,H,N] each
 }
 
 static int bwd_impl(const void* Q, const void* K, const void* V, const void* O, const float* LSE,

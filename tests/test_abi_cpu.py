@@ -79,7 +79,7 @@ def test_bwd_validation(lib):
     assert _bwd(lib, dtype=7) == E_DTYPE
     assert _bwd(lib, dq=0x7004) == E_ALIGN
     need = pkg.spark_mha_bwd_workspace_bytes(1, 1, 128, 64, 0)
-    assert need == 128 * 4
+    assert need == 2 * 128 * 4
     assert _bwd(lib, ws_bytes=need - 1) == E_WS
     assert _bwd(lib, fn="spark_mha_bwd_marked", extra=(None,)) == E_NULL
     evs = (ctypes.c_void_p * 4)(1, 2, None, 4)
@@ -87,7 +87,7 @@ def test_bwd_validation(lib):
 
 
 def test_workspace_bytes(lib):
-    assert pkg.spark_mha_bwd_workspace_bytes(4, 16, 4096, 128, 1) == 4 * 16 * 4096 * 4
+    assert pkg.spark_mha_bwd_workspace_bytes(4, 16, 4096, 128, 1) == 2 * 4 * 16 * 4096 * 4
     assert pkg.spark_mha_bwd_workspace_bytes(4, 16, 4096, 100, 1) == 0
     assert pkg.spark_mha_bwd_workspace_bytes(0, 16, 4096, 128, 1) == 0
 
