@@ -1,27 +1,32 @@
 // Attention backward for gfx950 (paper Sec. 3.3, Eq. 4), three kernels on one stream:
 //
-//   mha_bwd_dot_kernel  : D_i = sum_k dO_ik O_ik                 (the paper's "dPsum")
-//   mha_bwd_dkdv_kernel : one workgroup per tile of 128 keys, loops over query tiles,
-//                         recomputes P = exp(S - LSE), accumulates dV = P^T dO and
-//                         dK = scale * dS^T Q in registers, writes them once (as in Sec. 3.3,
-//                         where each thread block owns a slice of dK and dV).
-//   mha_bwd_dq_kernel   : one workgroup per tile of 128 queries, loops over key tiles,
-//                         recomputes P and dS and accumulates dQ = scale * dS K in registers.
+//   mha_bwd_dot_kernel       : D_i = sum_k dO_ik O_ik (the paper's "dPsum"), and LSE*log2(e)
+//   mha_bwd_dkdv_kernel      : one workgroup per tile of 128 keys, loops over query tiles,
+//   mha_bwd_dkdv_pipe_kernel   recomputes P = exp(S - LSE), accumulates dV = P^T dO and
+//                              dK = scale * dS^T Q in registers, writes them once (as in
+//                              Sec. 3.3, where each thread block owns a slice of dK and dV).
+//                              The first form runs two workgroups per CU (d = 64); the second
+//                              is software-pipelined inside the wave (d = 128, where the
+//                              accumulators leave room for one wave per SIMD only).
+//   mha_bwd_dq_kernel        : one workgroup per tile of 128 queries, loops over key tiles,
+//                              recomputes P and dS and accumulates dQ = scale * dS K.
 //
 // The paper adds every block's dQ contribution into HBM with atomic adds.  Here dQ has its
 // own pass with the forward's loop structure instead: it costs two recomputed contractions
 // (7 executed for 5 counted) but needs no fp32 dQ buffer to zero and convert, no atomics, and
-// gives bitwise reproducible gradients.
+// gives bitwise reproducible gradients.  (With 128 keys per workgroup the atomic variant would
+// add N/128 fp32 read-modify-writes per dQ element: 2.2 GB of atomic traffic for the
+// N = 4096, d = 128, 64-head causal case, more than the two recomputed contractions cost.)
 //
-// Register layouts follow mma_gfx950.hpp.  In the dK/dV kernel the score tile is computed as
+// Register layouts follow mma_gfx950.hpp.  In the dK/dV kernels the score tile is computed as
 // S = Q K^T (lane = key column, registers = query rows) so that P and dS, packed to 16 bits,
 // are directly the B operands of dV^T = dO^T P and dK^T = Q^T dS; the dO^T / Q^T operands
 // come from the row-major LDS tiles through transposing reads.  In the dQ kernel everything
 // is transposed as in the forward (lane = query column), so LSE_i and D_i are per-lane
 // scalars and dS^T is directly the B operand of dQ^T = K^T dS^T.
 #pragma once
-#include "fwd_kernel.hpp"
 #include "mma_gfx950.hpp"
+#include "tiles_gfx950.hpp"
 
 namespace spark {
 
@@ -56,144 +61,9 @@ __global__ __launch_bounds__(256) void mha_bwd_dot_kernel(const T* __restrict__ 
 }
 
 // ---------------------------------------------------------------------------------------
-// Shared pieces
-// ---------------------------------------------------------------------------------------
-
-// Copy ROWS x D 16-bit elements (rows r0.., clamped to N-1) from a row-major global matrix
-// into registers, 16 bytes per thread per step, and from registers into a padded LDS tile.
-template <int D, int ROWS, typename T>
-static __device__ __forceinline__ void tile_g2r(const T* __restrict__ base, int r0, int N, int tid,
-                                                u32x4 (&reg)[ROWS * (D / 8) / 256]) {
-  constexpr int CPR = D / 8;
-#pragma unroll
-  for (int i = 0; i < ROWS * CPR / 256; ++i) {
-    const int c = tid + 256 * i;
-    const int row = c / CPR, cc = c % CPR;
-    int grow = r0 + row;
-    grow = grow < N ? grow : N - 1;
-    reg[i] = *reinterpret_cast<const u32x4*>(base + (size_t)grow * D + cc * 8);
-  }
-}
-
-template <int D, int ROWS, int STRIDE>
-static __device__ __forceinline__ void tile_r2s(SPARK_LDS char* dst, int tid,
-                                                const u32x4 (&reg)[ROWS * (D / 8) / 256]) {
-  constexpr int CPR = D / 8;
-#pragma unroll
-  for (int i = 0; i < ROWS * CPR / 256; ++i) {
-    const int c = tid + 256 * i;
-    const int row = c / CPR, cc = c % CPR;
-    lds_write(dst, row * STRIDE + cc * 16, reg[i]);
-  }
-}
-
-// Write a wave's transposed accumulator (D x 32, lane = column) times `mul` as 32 rows of D
-// 16-bit values: through the wave's LDS slice `ob`, then 16-byte row stores for rows < N.
-template <typename T, int D, int OSTR>
-static __device__ __forceinline__ void store_transposed(const f32x16 (&acc)[D / 32], float mul,
-                                                        SPARK_LDS char* ob, T* __restrict__ out,
-                                                        int row0, int N, int lane) {
-  using v4 = typename Frag<T>::v4;
-  constexpr int CPR = D / 8;
-  constexpr int RPP = 64 / CPR;
-  const int g = lane >> 5, c32 = lane & 31;
-#pragma unroll
-  for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-    for (int r4 = 0; r4 < 4; ++r4) {
-      v4 pk;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) pk[e] = (T)(acc[dt][r4 * 4 + e] * mul);
-      lds_write(ob, c32 * OSTR + (dt * 32 + 8 * r4 + 4 * g) * 2, pk);
-    }
-#pragma unroll
-  for (int p = 0; p < 32 / RPP; ++p) {
-    const int row = p * RPP + lane / CPR, cc = lane % CPR;
-    const u32x4 v = lds_read16<u32x4>(ob, row * OSTR + cc * 16);
-    if (row0 + row < N) *reinterpret_cast<u32x4*>(out + (size_t)(row0 + row) * D + cc * 8) = v;
-  }
-}
-
-// ---------------------------------------------------------------------------------------
-// Swizzled LDS tiles.  A tile that is read both row-wise (16 bytes of one row per lane: A/B
-// operands contracted over d) and transposed (ds_read_b64_tr_b16 over 4 rows x 64 bytes)
-// cannot be made conflict-free by padding alone, so rows are unpadded (2*D bytes) and the
-// 16-byte chunk index is XORed with a function of the row:
-//   D = 128 (16 chunks/row):  f(r) = ((r & 3) << 2) | ((r >> 2) & 3)
-//   D =  64 ( 8 chunks/row):  x = (r >> 1) & 7,  f = ((x & 1) << 2) | ((x >> 1) & 3)
-// 16 consecutive rows at one logical chunk then fall into 16 different 16-byte bank groups,
-// and the 4 rows x 4 chunks of a transposing read into 16 different ones as well.  f depends
-// on r mod 16 only, so per-lane offsets are computed once and every tile / sub-tile / k-step
-// displacement is an immediate.
-// ---------------------------------------------------------------------------------------
-template <int D>
-static __device__ __forceinline__ int swz(int row) {
-  if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
-  const int x = (row >> 1) & 7;
-  return ((x & 1) << 2) | ((x >> 1) & 3);
-}
-template <int D>
-static __device__ __forceinline__ int swz_off(int row, int chunk) {
-  return row * (2 * D) + ((chunk ^ swz<D>(row)) << 4);
-}
-
-// registers -> swizzled tile (thread t owns chunk t of every group of 256 chunks)
-template <int D, int ROWS>
-static __device__ __forceinline__ void tile_r2s_swz(SPARK_LDS char* dst, int tid,
-                                                    const u32x4 (&reg)[ROWS * (D / 8) / 256]) {
-  constexpr int CPR = D / 8;
-#pragma unroll
-  for (int i = 0; i < ROWS * CPR / 256; ++i) {
-    const int c = tid + 256 * i;
-    lds_write(dst, swz_off<D>(c / CPR, c % CPR), reg[i]);
-  }
-}
-
-// global (buffer view) -> registers, rows r0.. of a [N][D] matrix; rows past N read as zero
-template <int D, int ROWS>
-static __device__ __forceinline__ void tile_b2r(const BufView& view, int r0, int tid,
-                                                u32x4 (&reg)[ROWS * (D / 8) / 256]) {
-#pragma unroll
-  for (int i = 0; i < ROWS * (D / 8) / 256; ++i)
-    reg[i] = view.load16(tid * 16 + i * 4096, (uint32_t)r0 * (D * 2));
-}
-
-// Per-lane byte offsets into a swizzled tile.
-//   row[ks]   : 16-byte row read, row c32, logical chunk 2*ks + g      (A/B operand over d)
-//   tr[h][dt] : transposing read for d-tile dt, rows 8h + 4g + i16/4   (operand over rows)
-// Add (multiple of 16 rows) * 2*D bytes for other sub-tiles; the swizzle is unchanged by that.
-template <int D> struct SwzLane {
-  int row[D / 16];
-  int tr[2][D / 32];
-  // `bias` is added to every offset (a region in front of the tiles), so that all later
-  // displacements stay small enough for the 16-bit immediate of the DS instructions.
-  __device__ __forceinline__ explicit SwzLane(int lane, int bias = 0) {
-    const int g = lane >> 5, c32 = lane & 31, i16 = lane & 15;
-#pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) row[ks] = bias + swz_off<D>(c32, 2 * ks + g);
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt)
-        tr[h][dt] = bias + swz_off<D>(8 * h + 4 * g + (i16 >> 2), dt * 4 + ((c32 >> 4) << 1) + ((i16 & 3) >> 1)) +
-                    (i16 & 1) * 8;
-  }
-};
-
-template <typename T>
-static __device__ __forceinline__ typename Frag<T>::v8 read_tr_pair(SPARK_LDS const char* tile, int off_lo,
-                                                                   int off_hi) {
-  using v8 = typename Frag<T>::v8;
-  using v4 = typename Frag<T>::v4;
-  const v4 lo = lds_read_tr8<v4>(tile, off_lo);
-  const v4 hi = lds_read_tr8<v4>(tile, off_hi);
-  return join4<v8, v4>(lo, hi);
-}
-
-template <int V> struct IntC { static constexpr int value = V; };
-
-// ---------------------------------------------------------------------------------------
-// dK, dV
+// dK, dV (used at d = 64): two workgroups per CU, so one workgroup's MFMAs overlap the
+// other's softmax arithmetic and LDS latency.  The row statistics are stored negated and in
+// the units of the raw scores and initialise the MFMA accumulators.
 // ---------------------------------------------------------------------------------------
 template <int D> struct BwdKvCfg {
   static constexpr int BN = 128;  // keys per workgroup (32 per wave)
@@ -237,181 +107,181 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_kernel(
   const BufView qview(Q + head_off, (uint32_t)N * D * 2), doview(dO + head_off, (uint32_t)N * D * 2);
 
   for (int rep = 0; rep < (CAUSAL ? 2 : 1); ++rep) {
-  const int kt = CAUSAL ? (rep == 0 ? item : nkt - 1 - item) : item;  // the long tile first
-  if (CAUSAL && rep == 1) {
-    if (kt == item) break;  // odd tile count: the middle tile has no partner
-    __syncthreads();        // the first tile's epilogue is done with the LDS
-  }
-  const int k0w = kt * C::BN + wave * 32;  // first key of this wave
-  const int krow = k0w + c32;
-  const int krow_c = krow < N ? krow : N - 1;
-
-  v8 kf[KS], vf[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    kf[ks] = *reinterpret_cast<const v8*>(K + head_off + (size_t)krow_c * D + ks * 16 + g * 8);
-    vf[ks] = *reinterpret_cast<const v8*>(V + head_off + (size_t)krow_c * D + ks * 16 + g * 8);
-  }
-
-  f32x16 dk[DT], dv[DT];
-#pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { dk[dt][r] = 0.f; dv[dt][r] = 0.f; }
-
-  const int ns = (N + C::BM - 1) / C::BM;                 // query stages in the sequence
-  const int s_begin = CAUSAL ? (kt * C::BN) / C::BM : 0;  // earlier queries see none of this tile
-
-  // Per-lane LDS read offsets of the current buffer; switching buffers is one XOR each.
-  SwzLane<D> off(lane);
-  int stat_off = 2 * C::STAGE + 16 * g;  // float4 of rows 4g.. in the current stat block
-  const float neg_inv_scale = -1.0f / scale;
-
-  u32x4 qreg[NLD], doreg[NLD];
-  float statreg = 0.f;
-  auto load_stage = [&](int m) {
-    tile_b2r<D, C::BM>(qview, m * C::BM, tid, qreg);
-    tile_b2r<D, C::BM>(doview, m * C::BM, tid, doreg);
-    if (tid < 2 * C::BM) {
-      const int row = m * C::BM + (tid & (C::BM - 1));
-      // The statistics are stored negated and in the units of the raw scores, so that they
-      // can initialise the MFMA accumulators: S - LSE/scale and dP - D come out of the
-      // contractions directly.  Rows past the end get -inf (P = 0 there) and D = 0.
-      // raw values only: any arithmetic on them here would force a wait for the loads
-      if (tid < C::BM)
-        statreg = row < N ? LSEh[row] : INFINITY;
-      else
-        statreg = row < N ? Dh[row] : 0.f;
+    const int kt = CAUSAL ? (rep == 0 ? item : nkt - 1 - item) : item;  // the long tile first
+    if (CAUSAL && rep == 1) {
+      if (kt == item) break;  // odd tile count: the middle tile has no partner
+      __syncthreads();        // the first tile's epilogue is done with the LDS
     }
-  };
-  auto store_stage = [&](int buf) {
-    SPARK_LDS char* sb = smem + buf * C::STAGE;
-    tile_r2s_swz<D, C::BM>(sb, tid, qreg);
-    tile_r2s_swz<D, C::BM>(sb + C::TILE, tid, doreg);
-    if (tid < 2 * C::BM)
-      lds_write(smem + 2 * C::STAGE + buf * C::STAT, tid * 4, statreg * (tid < C::BM ? neg_inv_scale : -1.0f));
-  };
+    const int k0w = kt * C::BN + wave * 32;  // first key of this wave
+    const int krow = k0w + c32;
+    const int krow_c = krow < N ? krow : N - 1;
 
-  load_stage(s_begin);
-  wait_vmem_all();  // K/V fragments and the first stage are in registers before the loop
+    v8 kf[KS], vf[KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(kf[ks]), "+v"(vf[ks]));
-  store_stage(0);
-  __syncthreads();
-
-  for (int m = s_begin; m < ns; ++m) {
-    const int buf = (m - s_begin) & 1;
-    if (m + 1 < ns) load_stage(m + 1);
-
-    SPARK_LDS const char* qb = smem;             // + off.* (which carry the buffer bit)
-    SPARK_LDS const char* dob = smem + C::TILE;
-
-#pragma unroll
-    for (int sub = 0; sub < C::BM / 32; ++sub) {
-      const int q0s = m * C::BM + sub * 32;
-      if (CAUSAL && q0s + 31 < k0w) continue;  // every query here precedes every key of the wave
-      if (q0s >= N) continue;
-      constexpr int NG = KS / 2;
-      const int suboff = sub * 32 * C::ROWB;
-
-      // S - LSE/scale = Q K^T - LSE/scale and dP - D = dO V^T - D (lane = key column, registers
-      // = query rows): the accumulators start from the negated row statistics.  Q / dO row
-      // fragments are read two k-steps ahead of the MFMAs that consume them.
-      v8 fa[2][4];
-      auto load_agroup = [&](int gi) {
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          fa[gi & 1][2 * e] = lds_read16<v8>(qb, off.row[2 * gi + e] + suboff);
-          fa[gi & 1][2 * e + 1] = lds_read16<v8>(dob, off.row[2 * gi + e] + suboff);
-        }
-      };
-      load_agroup(0);
-      f32x16 s, dp;
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int o = stat_off + (sub * 32 + 8 * r4) * 4;
-        const f32x4 l4 = lds_read16<f32x4>(smem, o);
-        const f32x4 d4 = lds_read16<f32x4>(smem, o + C::BM * 4);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { s[r4 * 4 + e] = l4[e]; dp[r4 * 4 + e] = d4[e]; }
-      }
-      load_agroup(1);
-      sched_fence();
-#pragma unroll
-      for (int gi = 0; gi < NG; ++gi) {
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          s = F::mfma(fa[gi & 1][2 * e], kf[2 * gi + e], s);
-          dp = F::mfma(fa[gi & 1][2 * e + 1], vf[2 * gi + e], dp);
-        }
-        if (gi + 2 < NG) load_agroup(gi + 2);
-        sched_fence();
-      }
-
-      // Transposed dO / Q fragments, 4 at a time (one 16-query step of two d-tiles), two groups
-      // ahead of the MFMAs; the first two groups are requested before the softmax arithmetic.
-      constexpr int NTG = 2 * (DT / 2);  // groups: (kk, dt pair)
-      v8 ft[2][4];
-      auto load_tgroup = [&](int tg) {
-        const int kk = tg / (DT / 2), dt0 = 2 * (tg % (DT / 2));
-        const int o = suboff + kk * 16 * C::ROWB;
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          ft[tg & 1][2 * e] = read_tr_pair<T>(dob, off.tr[0][dt0 + e] + o, off.tr[1][dt0 + e] + o);
-          ft[tg & 1][2 * e + 1] = read_tr_pair<T>(qb, off.tr[0][dt0 + e] + o, off.tr[1][dt0 + e] + o);
-        }
-      };
-      load_tgroup(0);
-      load_tgroup(1);
-      sched_fence();
-      asm volatile("" : "+v"(s), "+v"(dp));  // keep the score tiles in VALU-readable registers
-
-      float p[16], ds[16];
-      const bool need_mask = CAUSAL && q0s < k0w + 31;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float pe = __builtin_amdgcn_exp2f(s[r] * scale_log2);
-        if (need_mask && krow > q0s + 8 * (r / 4) + 4 * g + (r % 4)) pe = 0.f;
-        p[r] = pe;
-        ds[r] = pe * dp[r];
-      }
-      v8 pf[2], dsf[2];
-#pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-        pf[kk] = pack8<T>(&p[kk * 8]);
-        dsf[kk] = pack8<T>(&ds[kk * 8]);
-      }
-      sched_fence();
-
-      // dV^T += dO^T P and dK^T += Q^T dS
-#pragma unroll
-      for (int tg = 0; tg < NTG; ++tg) {
-        const int kk = tg / (DT / 2), dt0 = 2 * (tg % (DT / 2));
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          dv[dt0 + e] = F::mfma(ft[tg & 1][2 * e], pf[kk], dv[dt0 + e]);
-          dk[dt0 + e] = F::mfma(ft[tg & 1][2 * e + 1], dsf[kk], dk[dt0 + e]);
-        }
-        if (tg + 2 < NTG) load_tgroup(tg + 2);
-        sched_fence();
-      }
+    for (int ks = 0; ks < KS; ++ks) {
+      kf[ks] = *reinterpret_cast<const v8*>(K + head_off + (size_t)krow_c * D + ks * 16 + g * 8);
+      vf[ks] = *reinterpret_cast<const v8*>(V + head_off + (size_t)krow_c * D + ks * 16 + g * 8);
     }
 
-    if (m + 1 < ns) store_stage(buf ^ 1);
-    // switch the read offsets to the other buffer
+    f32x16 dk[DT], dv[DT];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) off.row[ks] ^= C::STAGE;
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+      for (int r = 0; r < 16; ++r) { dk[dt][r] = 0.f; dv[dt][r] = 0.f; }
+
+    const int ns = (N + C::BM - 1) / C::BM;                 // query stages in the sequence
+    const int s_begin = CAUSAL ? (kt * C::BN) / C::BM : 0;  // earlier queries see none of this tile
+
+    // Per-lane LDS read offsets of the current buffer; switching buffers is one XOR each.
+    SwzLane<D> off(lane);
+    int stat_off = 2 * C::STAGE + 16 * g;  // float4 of rows 4g.. in the current stat block
+    const float neg_inv_scale = -1.0f / scale;
+
+    u32x4 qreg[NLD], doreg[NLD];
+    float statreg = 0.f;
+    auto load_stage = [&](int m) {
+      tile_b2r<D, C::BM>(qview, m * C::BM, tid, qreg);
+      tile_b2r<D, C::BM>(doview, m * C::BM, tid, doreg);
+      if (tid < 2 * C::BM) {
+        const int row = m * C::BM + (tid & (C::BM - 1));
+        // The statistics are stored negated and in the units of the raw scores, so that they
+        // can initialise the MFMA accumulators: S - LSE/scale and dP - D come out of the
+        // contractions directly.  Rows past the end get -inf (P = 0 there) and D = 0.
+        // raw values only: any arithmetic on them here would force a wait for the loads
+        if (tid < C::BM)
+          statreg = row < N ? LSEh[row] : INFINITY;
+        else
+          statreg = row < N ? Dh[row] : 0.f;
+      }
+    };
+    auto store_stage = [&](int buf) {
+      SPARK_LDS char* sb = smem + buf * C::STAGE;
+      tile_r2s_swz<D, C::BM>(sb, tid, qreg);
+      tile_r2s_swz<D, C::BM>(sb + C::TILE, tid, doreg);
+      if (tid < 2 * C::BM)
+        lds_write(smem + 2 * C::STAGE + buf * C::STAT, tid * 4, statreg * (tid < C::BM ? neg_inv_scale : -1.0f));
+    };
+
+    load_stage(s_begin);
+    wait_vmem_all();  // K/V fragments and the first stage are in registers before the loop
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) off.tr[h][dt] ^= C::STAGE;
-    stat_off ^= C::STAT;
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(kf[ks]), "+v"(vf[ks]));
+    store_stage(0);
     __syncthreads();
-  }
 
-  SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
-  store_transposed<T, D, C::OSTR>(dk, scale, ob, dK + head_off, k0w, N, lane);
-  store_transposed<T, D, C::OSTR>(dv, 1.0f, ob, dV + head_off, k0w, N, lane);
+    for (int m = s_begin; m < ns; ++m) {
+      const int buf = (m - s_begin) & 1;
+      if (m + 1 < ns) load_stage(m + 1);
+
+      SPARK_LDS const char* qb = smem;             // + off.* (which carry the buffer bit)
+      SPARK_LDS const char* dob = smem + C::TILE;
+
+#pragma unroll
+      for (int sub = 0; sub < C::BM / 32; ++sub) {
+        const int q0s = m * C::BM + sub * 32;
+        if (CAUSAL && q0s + 31 < k0w) continue;  // every query here precedes every key of the wave
+        if (q0s >= N) continue;
+        constexpr int NG = KS / 2;
+        const int suboff = sub * 32 * C::ROWB;
+
+        // S - LSE/scale = Q K^T - LSE/scale and dP - D = dO V^T - D (lane = key column, registers
+        // = query rows): the accumulators start from the negated row statistics.  Q / dO row
+        // fragments are read two k-steps ahead of the MFMAs that consume them.
+        v8 fa[2][4];
+        auto load_agroup = [&](int gi) {
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            fa[gi & 1][2 * e] = lds_read16<v8>(qb, off.row[2 * gi + e] + suboff);
+            fa[gi & 1][2 * e + 1] = lds_read16<v8>(dob, off.row[2 * gi + e] + suboff);
+          }
+        };
+        load_agroup(0);
+        f32x16 s, dp;
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int o = stat_off + (sub * 32 + 8 * r4) * 4;
+          const f32x4 l4 = lds_read16<f32x4>(smem, o);
+          const f32x4 d4 = lds_read16<f32x4>(smem, o + C::BM * 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { s[r4 * 4 + e] = l4[e]; dp[r4 * 4 + e] = d4[e]; }
+        }
+        load_agroup(1);
+        sched_fence();
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi) {
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            s = F::mfma(fa[gi & 1][2 * e], kf[2 * gi + e], s);
+            dp = F::mfma(fa[gi & 1][2 * e + 1], vf[2 * gi + e], dp);
+          }
+          if (gi + 2 < NG) load_agroup(gi + 2);
+          sched_fence();
+        }
+
+        // Transposed dO / Q fragments, 4 at a time (one 16-query step of two d-tiles), two groups
+        // ahead of the MFMAs; the first two groups are requested before the softmax arithmetic.
+        constexpr int NTG = 2 * (DT / 2);  // groups: (kk, dt pair)
+        v8 ft[2][4];
+        auto load_tgroup = [&](int tg) {
+          const int kk = tg / (DT / 2), dt0 = 2 * (tg % (DT / 2));
+          const int o = suboff + kk * 16 * C::ROWB;
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            ft[tg & 1][2 * e] = read_tr_pair<T>(dob, off.tr[0][dt0 + e] + o, off.tr[1][dt0 + e] + o);
+            ft[tg & 1][2 * e + 1] = read_tr_pair<T>(qb, off.tr[0][dt0 + e] + o, off.tr[1][dt0 + e] + o);
+          }
+        };
+        load_tgroup(0);
+        load_tgroup(1);
+        sched_fence();
+        asm volatile("" : "+v"(s), "+v"(dp));  // keep the score tiles in VALU-readable registers
+
+        float p[16], ds[16];
+        const bool need_mask = CAUSAL && q0s < k0w + 31;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float pe = __builtin_amdgcn_exp2f(s[r] * scale_log2);
+          if (need_mask && krow > q0s + 8 * (r / 4) + 4 * g + (r % 4)) pe = 0.f;
+          p[r] = pe;
+          ds[r] = pe * dp[r];
+        }
+        v8 pf[2], dsf[2];
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+          pf[kk] = pack8<T>(&p[kk * 8]);
+          dsf[kk] = pack8<T>(&ds[kk * 8]);
+        }
+        sched_fence();
+
+        // dV^T += dO^T P and dK^T += Q^T dS
+#pragma unroll
+        for (int tg = 0; tg < NTG; ++tg) {
+          const int kk = tg / (DT / 2), dt0 = 2 * (tg % (DT / 2));
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            dv[dt0 + e] = F::mfma(ft[tg & 1][2 * e], pf[kk], dv[dt0 + e]);
+            dk[dt0 + e] = F::mfma(ft[tg & 1][2 * e + 1], dsf[kk], dk[dt0 + e]);
+          }
+          if (tg + 2 < NTG) load_tgroup(tg + 2);
+          sched_fence();
+        }
+      }
+
+      if (m + 1 < ns) store_stage(buf ^ 1);
+      // switch the read offsets to the other buffer
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) off.row[ks] ^= C::STAGE;
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) off.tr[h][dt] ^= C::STAGE;
+      stat_off ^= C::STAT;
+      __syncthreads();
+    }
+
+    SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
+    store_transposed<T, D, C::OSTR>(dk, scale, ob, dK + head_off, k0w, N, lane);
+    store_transposed<T, D, C::OSTR>(dv, 1.0f, ob, dV + head_off, k0w, N, lane);
   }  // rep
 }
 
@@ -444,26 +314,6 @@ template <int D> struct BwdKvPipeCfg {
   static_assert(4 * 32 * OSTR <= SLOTS * STAGE, "epilogue staging must fit");
 };
 
-// Direct global->LDS copy of a swizzled ROWS x D tile: wave w of the 4 waves fills the 1 KB
-// blocks w, w+4, ... of the tile; lane l writes bytes [16 l, 16 l + 16) of its block, so it
-// fetches the logical chunk that the swizzle places there.  `lane_src` is that per-lane source
-// offset for block `wave` (the later blocks are a multiple of 16 rows further on, where the
-// swizzle repeats).  Rows past the end of the matrix arrive as zeros.
-template <int D>
-static __device__ __forceinline__ uint32_t dma_lane_src(int wave, int lane) {
-  const int byte = wave * 1024 + lane * 16;
-  const int row = byte / (2 * D), pc = (byte % (2 * D)) >> 4;
-  return (uint32_t)(row * (2 * D) + ((pc ^ swz<D>(row)) << 4));
-}
-template <int D, int ROWS>
-static __device__ __forceinline__ void tile_dma(const BufView& view, int r0, SPARK_LDS char* dst,
-                                                int wave, uint32_t lane_src) {
-  static_assert((4 * 1024 / (2 * D)) % 16 == 0, "blocks of one wave must be 16 rows apart");
-#pragma unroll
-  for (int i = 0; i < ROWS * 2 * D / 4096; ++i)
-    view.load16_to_lds(dst + (i * 4 + wave) * 1024, lane_src, (uint32_t)r0 * (2 * D) + i * 4096);
-}
-
 template <typename T, int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
@@ -492,243 +342,243 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
   const float scale_log2 = scale * 1.4426950408889634f;
 
   for (int rep = 0; rep < (CAUSAL ? 2 : 1); ++rep) {
-  const int kt = CAUSAL ? (rep == 0 ? item : nkt - 1 - item) : item;  // the long tile first
-  if (CAUSAL && rep == 1) {
-    if (kt == item) break;  // odd tile count: the middle tile has no partner
-    __syncthreads();        // the first tile's epilogue is done with the LDS
-  }
-  const int k0w = kt * C::BN + wave * 32;
-  const int krow = k0w + c32;
-  const int krow_c = krow < N ? krow : N - 1;
-
-  v8 kf[KS], vf[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    kf[ks] = *reinterpret_cast<const v8*>(K + head_off + (size_t)krow_c * D + ks * 16 + g * 8);
-    vf[ks] = *reinterpret_cast<const v8*>(V + head_off + (size_t)krow_c * D + ks * 16 + g * 8);
-  }
-
-  f32x16 dk[DT], dv[DT];
-#pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { dk[dt][r] = 0.f; dv[dt][r] = 0.f; }
-
-  const int ns = (N + C::BM - 1) / C::BM;
-  const int s_begin = CAUSAL ? (kt * C::BN) / C::BM : 0;
-
-  const SwzLane<D> lane_off(lane);  // offsets inside slot 0
-  const int lane_stat = C::STAT0 + 16 * g;
-
-  // global -> LDS slot, asynchronously (completion is awaited with wait_vmem_all + barrier)
-  auto fetch_stage = [&](int m, int slot) {
-    SPARK_LDS char* sb = smem + slot * C::STAGE;
-    tile_dma<D, C::BM>(qview, m * C::BM, sb, wave, lane_src);
-    tile_dma<D, C::BM>(doview, m * C::BM, sb + C::TILE, wave, lane_src);
-    // 64 floats of LSE*log2(e) (wave 0) and of D (wave 1): 4 bytes per lane
-    SPARK_LDS char* st = smem + C::STAT0 + slot * C::STAT;
-    if (wave == 0) lview.load4_to_lds(st, lane * 4, (uint32_t)m * C::BM * 4);
-    if (wave == 1) dview.load4_to_lds(st + C::BM * 4, lane * 4, (uint32_t)m * C::BM * 4);
-  };
-
-  // LDS read offsets of the step whose scores are being formed (row reads, statistics) ...
-  int rowA[KS], statA;
-  // ... and of the step whose dV / dK are being accumulated (transposing reads)
-  int trC[2][DT];
-  auto point_A = [&](int slot) {
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) rowA[ks] = lane_off.row[ks] + slot * C::STAGE;
-    statA = lane_stat + slot * C::STAT;
-  };
-  auto point_C = [&](int slot) {
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) trC[h][dt] = lane_off.tr[h][dt] + slot * C::STAGE;
-  };
-
-  v8 fa[2][4];
-  auto load_agroup = [&](int gi, int sub) {
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-      fa[gi & 1][2 * e] = lds_read16<v8>(smem, rowA[2 * gi + e] + sub * 32 * C::ROWB);
-      fa[gi & 1][2 * e + 1] = lds_read16<v8>(smem + C::TILE, rowA[2 * gi + e] + sub * 32 * C::ROWB);
+    const int kt = CAUSAL ? (rep == 0 ? item : nkt - 1 - item) : item;  // the long tile first
+    if (CAUSAL && rep == 1) {
+      if (kt == item) break;  // odd tile count: the middle tile has no partner
+      __syncthreads();        // the first tile's epilogue is done with the LDS
     }
-  };
-  // statistics of 8 of the 16 query rows a lane holds (half = 0: registers 0..7, 1: 8..15) of the
-  // step rowA / statA point at
-  auto load_stats = [&](f32x4 (&l)[2], f32x4 (&d)[2], int sub, int half) {
+    const int k0w = kt * C::BN + wave * 32;
+    const int krow = k0w + c32;
+    const int krow_c = krow < N ? krow : N - 1;
+
+    v8 kf[KS], vf[KS];
 #pragma unroll
-    for (int x = 0; x < 2; ++x) {
-      const int o = statA + (sub * 32 + 8 * (2 * half + x)) * 4;
-      l[x] = lds_read16<f32x4>(smem, o);
-      d[x] = lds_read16<f32x4>(smem, o + C::BM * 4);
+    for (int ks = 0; ks < KS; ++ks) {
+      kf[ks] = *reinterpret_cast<const v8*>(K + head_off + (size_t)krow_c * D + ks * 16 + g * 8);
+      vf[ks] = *reinterpret_cast<const v8*>(V + head_off + (size_t)krow_c * D + ks * 16 + g * 8);
     }
-  };
-  constexpr int NG = KS / 2;
-  constexpr int NTG = 2 * (DT / 2);
-  v8 ft[2][4];
-  auto load_tgroup = [&](int tg, int sub) {
-    const int kk = tg / (DT / 2), dt0 = 2 * (tg % (DT / 2));
-    const int o = sub * 32 * C::ROWB + kk * 16 * C::ROWB;
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-      ft[tg & 1][2 * e] = read_tr_pair<T>(smem + C::TILE, trC[0][dt0 + e] + o, trC[1][dt0 + e] + o);
-      ft[tg & 1][2 * e + 1] = read_tr_pair<T>(smem, trC[0][dt0 + e] + o, trC[1][dt0 + e] + o);
-    }
-  };
 
-  // One element of P and dS from finished scores: the unit of VALU work that is placed between
-  // MFMAs.  r8 = register index within the half (0..7).
-  auto softmax_elem = [&](const f32x16& s, const f32x16& dp, int half, int r8, const f32x4 (&l)[2],
-                          const f32x4 (&d)[2], int q0s, bool mask, float* p, float* ds) {
-    const int r = 8 * half + r8;
-    float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, -l[r8 >> 2][r8 & 3]));
-    if (mask) pe = krow > q0s + 8 * (r / 4) + 4 * g + (r % 4) ? 0.f : pe;
-    p[r8] = pe;
-    ds[r8] = pe * (dp[r] - d[r8 >> 2][r8 & 3]);
-  };
+    f32x16 dk[DT], dv[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { dk[dt][r] = 0.f; dv[dt][r] = 0.f; }
 
-  // ---- prologue: stages s_begin and s_begin+1 resident, scores of the first step formed ----
-  fetch_stage(s_begin, 0);
-  if (s_begin + 1 < ns) fetch_stage(s_begin + 1, 1);
-  wait_vmem_all();
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(kf[ks]), "+v"(vf[ks]));
-  __syncthreads();
+    const int ns = (N + C::BM - 1) / C::BM;
+    const int s_begin = CAUSAL ? (kt * C::BN) / C::BM : 0;
 
-  point_A(0);
-  point_C(0);
-  f32x16 sX, dpX, sY, dpY;
-  f32x4 lL[2], dL[2], lH[2], dH[2];  // statistics: first half of the next step / second half of the current
-#pragma unroll
-  for (int r = 0; r < 16; ++r) { sX[r] = 0.f; dpX[r] = 0.f; }
-  load_agroup(0, 0);
-  load_agroup(1, 0);
-  load_stats(lL, dL, 0, 0);
-#pragma unroll
-  for (int gi = 0; gi < NG; ++gi) {
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-      sX = F::mfma(fa[gi & 1][2 * e], kf[2 * gi + e], sX);
-      dpX = F::mfma(fa[gi & 1][2 * e + 1], vf[2 * gi + e], dpX);
-    }
-    if (gi + 2 < NG) load_agroup(gi + 2, 0);
-    sched_fence();
-  }
-  // The MFMAs deliver the scores in accumulation registers, which the VALU cannot use as
-  // operands, and a copy out of them stalls while any MFMA is executing (measured: reading them
-  // element by element between MFMAs serialises the two pipes completely).  So each finished
-  // score tile is copied to VALU registers in one burst, right after the region that formed it,
-  // and all softmax arithmetic works on the copies sV / dpV.
-  f32x16 sV = sX, dpV = dpX;
-  asm volatile("" : "+v"(sV), "+v"(dpV));
-  // P / dS operands of the current step: registers 0..7 (pfL, dsfL) are formed one region
-  // early, registers 8..15 (pfH, dsfH) while the next step's scores are on the matrix cores.
-  v8 pfL, dsfL;
-  {
-    float p[8], ds[8];
-#pragma unroll
-    for (int r = 0; r < 8; ++r) softmax_elem(sV, dpV, 0, r, lL, dL, s_begin * C::BM, CAUSAL, p, ds);
-    pfL = pack8<T>(p);
-    dsfL = pack8<T>(ds);
-  }
-  load_stats(lH, dH, 0, 1);
+    const SwzLane<D> lane_off(lane);  // offsets inside slot 0
+    const int lane_stat = C::STAT0 + 16 * g;
 
-  // One stage: steps (m, 0) and (m, 1).  On entry sX / dpX hold the scores of (m, 0), pfL / dsfL
-  // their first half and lH / dH the statistics of their second half; rowA and trC point at
-  // stage m.  On exit the same holds for (m+1, 0).
-  auto stage = [&](int m, int slot, bool mask) {
-    const int slot1 = slot == 2 ? 0 : slot + 1;
-    const int slot2 = slot1 == 2 ? 0 : slot1 + 1;
-    // stage m+2 goes into the slot that stage m-1 used; everybody left it before the last barrier
-    if (m + 2 < ns) fetch_stage(m + 2, slot2);
-
-    // One step.  cur: scores complete, first half of P / dS packed.  new: the step after it
-    // (sub_new inside the stage rowA / statA point at).
-    auto step = [&](f32x16& s_new, f32x16& dp_new, int sub_new, int q0_new, int sub_cur, int q0_cur) {
-      // ---- region 1: scores of the next step  ||  second half of P, dS of the current step ----
-      float p[8], ds[8];
-      load_stats(lL, dL, sub_new, 0);
-      load_tgroup(0, sub_cur);
-#pragma unroll
-      for (int i = 0; i < 4 * NG; ++i) {
-        const int gi = i / 4, e = (i / 2) & 1;
-        if ((i & 1) == 0)
-          s_new = F::mfma(fa[gi & 1][2 * e], kf[2 * gi + e], s_new);
-        else
-          dp_new = F::mfma(fa[gi & 1][2 * e + 1], vf[2 * gi + e], dp_new);
-        if ((i & 3) == 3 && gi + 2 < NG) load_agroup(gi + 2, sub_new);
-        if (i == 2 * NG) load_tgroup(1, sub_cur);
-        if (i & 1) softmax_elem(sV, dpV, 1, i / 2, lH, dH, q0_cur, mask, p, ds);
-        sched_fence();
-      }
-      const v8 pfH = pack8<T>(p), dsfH = pack8<T>(ds);
-      load_stats(lH, dH, sub_new, 1);
-      sched_fence();
-      sV = s_new;  // burst copy of the scores just formed (see above)
-      dpV = dp_new;
-      asm volatile("" : "+v"(sV), "+v"(dpV));
-      sched_fence();
-      // ---- region 2: dV, dK of the current step  ||  first half of P, dS of the next step ----
-#pragma unroll
-      for (int tg = 0; tg < NTG; ++tg) {
-        const int kk = tg / (DT / 2), dt0 = 2 * (tg % (DT / 2));
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          dv[dt0 + e] = F::mfma(ft[tg & 1][2 * e], kk ? pfH : pfL, dv[dt0 + e]);
-          dk[dt0 + e] = F::mfma(ft[tg & 1][2 * e + 1], kk ? dsfH : dsfL, dk[dt0 + e]);
-          softmax_elem(sV, dpV, 0, (8 / NTG) * tg + e, lL, dL, q0_new, mask, p, ds);
-          if (8 / NTG > 2) softmax_elem(sV, dpV, 0, (8 / NTG) * tg + 2 + e, lL, dL, q0_new, mask, p, ds);
-          sched_fence();
-        }
-        if (tg + 2 < NTG) load_tgroup(tg + 2, sub_cur);
-        sched_fence();
-      }
-      pfL = pack8<T>(p);
-      dsfL = pack8<T>(ds);
-      // materialise here: otherwise this arithmetic sinks to its use in the next step and
-      // runs there with no MFMA to hide it
-      asm volatile("" : "+v"(pfL), "+v"(dsfL));
+    // global -> LDS slot, asynchronously (completion is awaited with wait_vmem_all + barrier)
+    auto fetch_stage = [&](int m, int slot) {
+      SPARK_LDS char* sb = smem + slot * C::STAGE;
+      tile_dma<D, C::BM>(qview, m * C::BM, sb, wave, lane_src);
+      tile_dma<D, C::BM>(doview, m * C::BM, sb + C::TILE, wave, lane_src);
+      // 64 floats of LSE*log2(e) (wave 0) and of D (wave 1): 4 bytes per lane
+      SPARK_LDS char* st = smem + C::STAT0 + slot * C::STAT;
+      if (wave == 0) lview.load4_to_lds(st, lane * 4, (uint32_t)m * C::BM * 4);
+      if (wave == 1) dview.load4_to_lds(st + C::BM * 4, lane * 4, (uint32_t)m * C::BM * 4);
     };
 
-    // (m, 1) scores  ||  (m, 0) softmax; then (m, 0) dV / dK
+    // LDS read offsets of the step whose scores are being formed (row reads, statistics) ...
+    int rowA[KS], statA;
+    // ... and of the step whose dV / dK are being accumulated (transposing reads)
+    int trC[2][DT];
+    auto point_A = [&](int slot) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { sY[r] = 0.f; dpY[r] = 0.f; }
-    load_agroup(0, 1);
-    load_agroup(1, 1);
-    sched_fence();
-    step(sY, dpY, 1, m * C::BM + 32, 0, m * C::BM);
-    // (m+1, 0) scores  ||  (m, 1) softmax; then (m, 1) dV / dK
-    point_A(slot1);
+      for (int ks = 0; ks < KS; ++ks) rowA[ks] = lane_off.row[ks] + slot * C::STAGE;
+      statA = lane_stat + slot * C::STAT;
+    };
+    auto point_C = [&](int slot) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) trC[h][dt] = lane_off.tr[h][dt] + slot * C::STAGE;
+    };
+
+    v8 fa[2][4];
+    auto load_agroup = [&](int gi, int sub) {
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        fa[gi & 1][2 * e] = lds_read16<v8>(smem, rowA[2 * gi + e] + sub * 32 * C::ROWB);
+        fa[gi & 1][2 * e + 1] = lds_read16<v8>(smem + C::TILE, rowA[2 * gi + e] + sub * 32 * C::ROWB);
+      }
+    };
+    // statistics of 8 of the 16 query rows a lane holds (half = 0: registers 0..7, 1: 8..15) of the
+    // step rowA / statA point at
+    auto load_stats = [&](f32x4 (&l)[2], f32x4 (&d)[2], int sub, int half) {
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+        const int o = statA + (sub * 32 + 8 * (2 * half + x)) * 4;
+        l[x] = lds_read16<f32x4>(smem, o);
+        d[x] = lds_read16<f32x4>(smem, o + C::BM * 4);
+      }
+    };
+    constexpr int NG = KS / 2;
+    constexpr int NTG = 2 * (DT / 2);
+    v8 ft[2][4];
+    auto load_tgroup = [&](int tg, int sub) {
+      const int kk = tg / (DT / 2), dt0 = 2 * (tg % (DT / 2));
+      const int o = sub * 32 * C::ROWB + kk * 16 * C::ROWB;
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        ft[tg & 1][2 * e] = read_tr_pair<T>(smem + C::TILE, trC[0][dt0 + e] + o, trC[1][dt0 + e] + o);
+        ft[tg & 1][2 * e + 1] = read_tr_pair<T>(smem, trC[0][dt0 + e] + o, trC[1][dt0 + e] + o);
+      }
+    };
+
+    // One element of P and dS from finished scores: the unit of VALU work that is placed between
+    // MFMAs.  r8 = register index within the half (0..7).
+    auto softmax_elem = [&](const f32x16& s, const f32x16& dp, int half, int r8, const f32x4 (&l)[2],
+                            const f32x4 (&d)[2], int q0s, bool mask, float* p, float* ds) {
+      const int r = 8 * half + r8;
+      float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, -l[r8 >> 2][r8 & 3]));
+      if (mask) pe = krow > q0s + 8 * (r / 4) + 4 * g + (r % 4) ? 0.f : pe;
+      p[r8] = pe;
+      ds[r8] = pe * (dp[r] - d[r8 >> 2][r8 & 3]);
+    };
+
+    // ---- prologue: stages s_begin and s_begin+1 resident, scores of the first step formed ----
+    fetch_stage(s_begin, 0);
+    if (s_begin + 1 < ns) fetch_stage(s_begin + 1, 1);
+    wait_vmem_all();
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(kf[ks]), "+v"(vf[ks]));
+    __syncthreads();
+
+    point_A(0);
+    point_C(0);
+    f32x16 sX, dpX, sY, dpY;
+    f32x4 lL[2], dL[2], lH[2], dH[2];  // statistics: first half of the next step / second half of the current
 #pragma unroll
     for (int r = 0; r < 16; ++r) { sX[r] = 0.f; dpX[r] = 0.f; }
     load_agroup(0, 0);
     load_agroup(1, 0);
-    sched_fence();
-    step(sX, dpX, 0, (m + 1) * C::BM, 1, m * C::BM + 32);
+    load_stats(lL, dL, 0, 0);
+#pragma unroll
+    for (int gi = 0; gi < NG; ++gi) {
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        sX = F::mfma(fa[gi & 1][2 * e], kf[2 * gi + e], sX);
+        dpX = F::mfma(fa[gi & 1][2 * e + 1], vf[2 * gi + e], dpX);
+      }
+      if (gi + 2 < NG) load_agroup(gi + 2, 0);
+      sched_fence();
+    }
+    // The MFMAs deliver the scores in accumulation registers, which the VALU cannot use as
+    // operands, and a copy out of them stalls while any MFMA is executing (measured: reading them
+    // element by element between MFMAs serialises the two pipes completely).  So each finished
+    // score tile is copied to VALU registers in one burst, right after the region that formed it,
+    // and all softmax arithmetic works on the copies sV / dpV.
+    f32x16 sV = sX, dpV = dpX;
+    asm volatile("" : "+v"(sV), "+v"(dpV));
+    // P / dS operands of the current step: registers 0..7 (pfL, dsfL) are formed one region
+    // early, registers 8..15 (pfH, dsfH) while the next step's scores are on the matrix cores.
+    v8 pfL, dsfL;
+    {
+      float p[8], ds[8];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) softmax_elem(sV, dpV, 0, r, lL, dL, s_begin * C::BM, CAUSAL, p, ds);
+      pfL = pack8<T>(p);
+      dsfL = pack8<T>(ds);
+    }
+    load_stats(lH, dH, 0, 1);
 
-    point_C(slot1);
-    wait_vmem_all();  // stage m+2 has landed (it was requested a whole stage ago)
-    __syncthreads();
-  };
+    // One stage: steps (m, 0) and (m, 1).  On entry sX / dpX hold the scores of (m, 0), pfL / dsfL
+    // their first half and lH / dH the statistics of their second half; rowA and trC point at
+    // stage m.  On exit the same holds for (m+1, 0).
+    auto stage = [&](int m, int slot, bool mask) {
+      const int slot1 = slot == 2 ? 0 : slot + 1;
+      const int slot2 = slot1 == 2 ? 0 : slot1 + 1;
+      // stage m+2 goes into the slot that stage m-1 used; everybody left it before the last barrier
+      if (m + 2 < ns) fetch_stage(m + 2, slot2);
 
-  int m = s_begin, slot = 0;
-  if (CAUSAL) {  // the diagonal crosses the first two stages only
-    const int m_end = s_begin + 2 < ns ? s_begin + 2 : ns;
-    for (; m < m_end; ++m) {
-      stage(m, slot, true);
+      // One step.  cur: scores complete, first half of P / dS packed.  new: the step after it
+      // (sub_new inside the stage rowA / statA point at).
+      auto step = [&](f32x16& s_new, f32x16& dp_new, int sub_new, int q0_new, int sub_cur, int q0_cur) {
+        // ---- region 1: scores of the next step  ||  second half of P, dS of the current step ----
+        float p[8], ds[8];
+        load_stats(lL, dL, sub_new, 0);
+        load_tgroup(0, sub_cur);
+#pragma unroll
+        for (int i = 0; i < 4 * NG; ++i) {
+          const int gi = i / 4, e = (i / 2) & 1;
+          if ((i & 1) == 0)
+            s_new = F::mfma(fa[gi & 1][2 * e], kf[2 * gi + e], s_new);
+          else
+            dp_new = F::mfma(fa[gi & 1][2 * e + 1], vf[2 * gi + e], dp_new);
+          if ((i & 3) == 3 && gi + 2 < NG) load_agroup(gi + 2, sub_new);
+          if (i == 2 * NG) load_tgroup(1, sub_cur);
+          if (i & 1) softmax_elem(sV, dpV, 1, i / 2, lH, dH, q0_cur, mask, p, ds);
+          sched_fence();
+        }
+        const v8 pfH = pack8<T>(p), dsfH = pack8<T>(ds);
+        load_stats(lH, dH, sub_new, 1);
+        sched_fence();
+        sV = s_new;  // burst copy of the scores just formed (see above)
+        dpV = dp_new;
+        asm volatile("" : "+v"(sV), "+v"(dpV));
+        sched_fence();
+        // ---- region 2: dV, dK of the current step  ||  first half of P, dS of the next step ----
+#pragma unroll
+        for (int tg = 0; tg < NTG; ++tg) {
+          const int kk = tg / (DT / 2), dt0 = 2 * (tg % (DT / 2));
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            dv[dt0 + e] = F::mfma(ft[tg & 1][2 * e], kk ? pfH : pfL, dv[dt0 + e]);
+            dk[dt0 + e] = F::mfma(ft[tg & 1][2 * e + 1], kk ? dsfH : dsfL, dk[dt0 + e]);
+            softmax_elem(sV, dpV, 0, (8 / NTG) * tg + e, lL, dL, q0_new, mask, p, ds);
+            if (8 / NTG > 2) softmax_elem(sV, dpV, 0, (8 / NTG) * tg + 2 + e, lL, dL, q0_new, mask, p, ds);
+            sched_fence();
+          }
+          if (tg + 2 < NTG) load_tgroup(tg + 2, sub_cur);
+          sched_fence();
+        }
+        pfL = pack8<T>(p);
+        dsfL = pack8<T>(ds);
+        // materialise here: otherwise this arithmetic sinks to its use in the next step and
+        // runs there with no MFMA to hide it
+        asm volatile("" : "+v"(pfL), "+v"(dsfL));
+      };
+
+      // (m, 1) scores  ||  (m, 0) softmax; then (m, 0) dV / dK
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sY[r] = 0.f; dpY[r] = 0.f; }
+      load_agroup(0, 1);
+      load_agroup(1, 1);
+      sched_fence();
+      step(sY, dpY, 1, m * C::BM + 32, 0, m * C::BM);
+      // (m+1, 0) scores  ||  (m, 1) softmax; then (m, 1) dV / dK
+      point_A(slot1);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sX[r] = 0.f; dpX[r] = 0.f; }
+      load_agroup(0, 0);
+      load_agroup(1, 0);
+      sched_fence();
+      step(sX, dpX, 0, (m + 1) * C::BM, 1, m * C::BM + 32);
+
+      point_C(slot1);
+      wait_vmem_all();  // stage m+2 has landed (it was requested a whole stage ago)
+      __syncthreads();
+    };
+
+    int m = s_begin, slot = 0;
+    if (CAUSAL) {  // the diagonal crosses the first two stages only
+      const int m_end = s_begin + 2 < ns ? s_begin + 2 : ns;
+      for (; m < m_end; ++m) {
+        stage(m, slot, true);
+        slot = slot == 2 ? 0 : slot + 1;
+      }
+    }
+    for (; m < ns; ++m) {
+      stage(m, slot, false);
       slot = slot == 2 ? 0 : slot + 1;
     }
-  }
-  for (; m < ns; ++m) {
-    stage(m, slot, false);
-    slot = slot == 2 ? 0 : slot + 1;
-  }
 
-  SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
-  store_transposed<T, D, C::OSTR>(dk, scale, ob, dK + head_off, k0w, N, lane);
-  store_transposed<T, D, C::OSTR>(dv, 1.0f, ob, dV + head_off, k0w, N, lane);
+    SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
+    store_transposed<T, D, C::OSTR>(dk, scale, ob, dK + head_off, k0w, N, lane);
+    store_transposed<T, D, C::OSTR>(dv, 1.0f, ob, dV + head_off, k0w, N, lane);
   }  // rep
 }
 
@@ -774,148 +624,148 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
   const BufView kview(K + head_off, (uint32_t)N * D * 2), vview(V + head_off, (uint32_t)N * D * 2);
 
   for (int rep = 0; rep < (CAUSAL ? 2 : 1); ++rep) {
-  const int qt = CAUSAL ? (rep == 0 ? nqt - 1 - item : item) : item;  // the long tile first
-  if (CAUSAL && rep == 1) {
-    if (qt == nqt - 1 - item) break;  // odd tile count: the middle tile has no partner
-    __syncthreads();                  // the first tile's epilogue is done with the LDS
-  }
-  const int q0 = qt * C::BM + wave * 32;
-  const int qrow = q0 + c32;
-  const int qrow_c = qrow < N ? qrow : N - 1;
-
-  v8 qf[KS], dof[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    qf[ks] = *reinterpret_cast<const v8*>(Q + head_off + (size_t)qrow_c * D + ks * 16 + g * 8);
-    dof[ks] = *reinterpret_cast<const v8*>(dO + head_off + (size_t)qrow_c * D + ks * 16 + g * 8);
-  }
-  float lse2 = LSE[(size_t)head * N + qrow_c] * 1.4426950408889634f;
-  float Dq = Dws[(size_t)head * N + qrow_c];
-
-  int kv_end = N;
-  if (CAUSAL) {
-    const int lim = (qt + 1) * C::BM;
-    kv_end = lim < N ? lim : N;
-  }
-  const int nt = (kv_end + C::BN - 1) / C::BN;
-
-  SwzLane<D> off(lane);  // read offsets of the current buffer; switched by one XOR each
-
-  u32x4 kreg[NLD], vreg[NLD];
-  f32x16 dq[DT];
-#pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) dq[dt][r] = 0.f;
-
-  tile_b2r<D, C::BN>(kview, 0, tid, kreg);
-  tile_b2r<D, C::BN>(vview, 0, tid, vreg);
-  wait_vmem_all();  // Q / dO fragments and the row statistics are in registers before the loop
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]), "+v"(dof[ks]));
-  asm volatile("" : "+v"(lse2), "+v"(Dq));
-  tile_r2s_swz<D, C::BN>(smem, tid, kreg);
-  tile_r2s_swz<D, C::BN>(smem + C::TILE, tid, vreg);
-  __syncthreads();
-
-  for (int j = 0; j < nt; ++j) {
-    const int buf = j & 1;
-    if (j + 1 < nt) {
-      tile_b2r<D, C::BN>(kview, (j + 1) * C::BN, tid, kreg);
-      tile_b2r<D, C::BN>(vview, (j + 1) * C::BN, tid, vreg);
+    const int qt = CAUSAL ? (rep == 0 ? nqt - 1 - item : item) : item;  // the long tile first
+    if (CAUSAL && rep == 1) {
+      if (qt == nqt - 1 - item) break;  // odd tile count: the middle tile has no partner
+      __syncthreads();                  // the first tile's epilogue is done with the LDS
     }
-    const int k0 = j * C::BN;
-    if (!CAUSAL || k0 <= q0 + 31) {
-      SPARK_LDS const char* kb = smem;  // + off.* (which carry the buffer bit)
-      SPARK_LDS const char* vb = smem + C::TILE;
+    const int q0 = qt * C::BM + wave * 32;
+    const int qrow = q0 + c32;
+    const int qrow_c = qrow < N ? qrow : N - 1;
 
-      // S^T = K Q^T and dP^T = V dO^T (lane = query column, registers = keys); the row
-      // fragments of one k-step (MT key blocks x {K, V}) are read two steps ahead of the MFMAs.
-      constexpr int MT = C::BN / 32;  // 32-key blocks per tile
-      f32x16 s[MT], dp[MT];
+    v8 qf[KS], dof[KS];
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { s[mt][r] = 0.f; dp[mt][r] = 0.f; }
-      v8 fa[2][2 * MT];
-      auto load_agroup = [&](int ks) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          const int o = off.row[ks] + mt * 32 * C::ROWB;
-          fa[ks & 1][2 * mt] = lds_read16<v8>(kb, o);
-          fa[ks & 1][2 * mt + 1] = lds_read16<v8>(vb, o);
-        }
-      };
-      load_agroup(0);
-      load_agroup(1);
-      sched_fence();
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          s[mt] = F::mfma(fa[ks & 1][2 * mt], qf[ks], s[mt]);
-          dp[mt] = F::mfma(fa[ks & 1][2 * mt + 1], dof[ks], dp[mt]);
-        }
-        if (ks + 2 < KS) load_agroup(ks + 2);
-        sched_fence();
-      }
-
-      // K^T fragments of the first two 16-key steps fly during the softmax arithmetic
-      constexpr int NKK = C::BN / 16;
-      v8 ft[2][DT];
-      auto load_tgroup = [&](int kk) {
-        const int o = kk * 16 * C::ROWB;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-          ft[kk & 1][dt] = read_tr_pair<T>(kb, off.tr[0][dt] + o, off.tr[1][dt] + o);
-      };
-      load_tgroup(0);
-      load_tgroup(1);
-      sched_fence();
-
-      float ds[16 * MT];
-      const bool need_mask = (CAUSAL && k0 + C::BN - 1 > q0) || (k0 + C::BN > N);
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mt][r], scale_log2, -lse2));
-          if (need_mask) {
-            const int key = k0 + mt * 32 + 8 * (r / 4) + 4 * g + (r % 4);
-            const bool ok = key < N && (!CAUSAL || key <= qrow);
-            if (!ok) pe = 0.f;
-          }
-          ds[mt * 16 + r] = pe * (dp[mt][r] - Dq);
-        }
-      v8 dsf[NKK];
-#pragma unroll
-      for (int kk = 0; kk < NKK; ++kk) dsf[kk] = pack8<T>(&ds[kk * 8]);
-      sched_fence();
-
-      // dQ^T += K^T dS^T, 16 keys per step
-#pragma unroll
-      for (int kk = 0; kk < NKK; ++kk) {
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) dq[dt] = F::mfma(ft[kk & 1][dt], dsf[kk], dq[dt]);
-        if (kk + 2 < NKK) load_tgroup(kk + 2);
-        sched_fence();
-      }
+    for (int ks = 0; ks < KS; ++ks) {
+      qf[ks] = *reinterpret_cast<const v8*>(Q + head_off + (size_t)qrow_c * D + ks * 16 + g * 8);
+      dof[ks] = *reinterpret_cast<const v8*>(dO + head_off + (size_t)qrow_c * D + ks * 16 + g * 8);
     }
-    if (j + 1 < nt) {
-      tile_r2s_swz<D, C::BN>(smem + (buf ^ 1) * C::STAGE, tid, kreg);
-      tile_r2s_swz<D, C::BN>(smem + (buf ^ 1) * C::STAGE + C::TILE, tid, vreg);
+    float lse2 = LSE[(size_t)head * N + qrow_c] * 1.4426950408889634f;
+    float Dq = Dws[(size_t)head * N + qrow_c];
+
+    int kv_end = N;
+    if (CAUSAL) {
+      const int lim = (qt + 1) * C::BM;
+      kv_end = lim < N ? lim : N;
     }
+    const int nt = (kv_end + C::BN - 1) / C::BN;
+
+    SwzLane<D> off(lane);  // read offsets of the current buffer; switched by one XOR each
+
+    u32x4 kreg[NLD], vreg[NLD];
+    f32x16 dq[DT];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) off.row[ks] ^= C::STAGE;
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+      for (int r = 0; r < 16; ++r) dq[dt][r] = 0.f;
+
+    tile_b2r<D, C::BN>(kview, 0, tid, kreg);
+    tile_b2r<D, C::BN>(vview, 0, tid, vreg);
+    wait_vmem_all();  // Q / dO fragments and the row statistics are in registers before the loop
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) off.tr[h][dt] ^= C::STAGE;
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]), "+v"(dof[ks]));
+    asm volatile("" : "+v"(lse2), "+v"(Dq));
+    tile_r2s_swz<D, C::BN>(smem, tid, kreg);
+    tile_r2s_swz<D, C::BN>(smem + C::TILE, tid, vreg);
     __syncthreads();
-  }
 
-  SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
-  store_transposed<T, D, C::OSTR>(dq, scale, ob, dQ + head_off, q0, N, lane);
+    for (int j = 0; j < nt; ++j) {
+      const int buf = j & 1;
+      if (j + 1 < nt) {
+        tile_b2r<D, C::BN>(kview, (j + 1) * C::BN, tid, kreg);
+        tile_b2r<D, C::BN>(vview, (j + 1) * C::BN, tid, vreg);
+      }
+      const int k0 = j * C::BN;
+      if (!CAUSAL || k0 <= q0 + 31) {
+        SPARK_LDS const char* kb = smem;  // + off.* (which carry the buffer bit)
+        SPARK_LDS const char* vb = smem + C::TILE;
+
+        // S^T = K Q^T and dP^T = V dO^T (lane = query column, registers = keys); the row
+        // fragments of one k-step (MT key blocks x {K, V}) are read two steps ahead of the MFMAs.
+        constexpr int MT = C::BN / 32;  // 32-key blocks per tile
+        f32x16 s[MT], dp[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) { s[mt][r] = 0.f; dp[mt][r] = 0.f; }
+        v8 fa[2][2 * MT];
+        auto load_agroup = [&](int ks) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            const int o = off.row[ks] + mt * 32 * C::ROWB;
+            fa[ks & 1][2 * mt] = lds_read16<v8>(kb, o);
+            fa[ks & 1][2 * mt + 1] = lds_read16<v8>(vb, o);
+          }
+        };
+        load_agroup(0);
+        load_agroup(1);
+        sched_fence();
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            s[mt] = F::mfma(fa[ks & 1][2 * mt], qf[ks], s[mt]);
+            dp[mt] = F::mfma(fa[ks & 1][2 * mt + 1], dof[ks], dp[mt]);
+          }
+          if (ks + 2 < KS) load_agroup(ks + 2);
+          sched_fence();
+        }
+
+        // K^T fragments of the first two 16-key steps fly during the softmax arithmetic
+        constexpr int NKK = C::BN / 16;
+        v8 ft[2][DT];
+        auto load_tgroup = [&](int kk) {
+          const int o = kk * 16 * C::ROWB;
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt)
+            ft[kk & 1][dt] = read_tr_pair<T>(kb, off.tr[0][dt] + o, off.tr[1][dt] + o);
+        };
+        load_tgroup(0);
+        load_tgroup(1);
+        sched_fence();
+
+        float ds[16 * MT];
+        const bool need_mask = (CAUSAL && k0 + C::BN - 1 > q0) || (k0 + C::BN > N);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mt][r], scale_log2, -lse2));
+            if (need_mask) {
+              const int key = k0 + mt * 32 + 8 * (r / 4) + 4 * g + (r % 4);
+              const bool ok = key < N && (!CAUSAL || key <= qrow);
+              if (!ok) pe = 0.f;
+            }
+            ds[mt * 16 + r] = pe * (dp[mt][r] - Dq);
+          }
+        v8 dsf[NKK];
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) dsf[kk] = pack8<T>(&ds[kk * 8]);
+        sched_fence();
+
+        // dQ^T += K^T dS^T, 16 keys per step
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) {
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) dq[dt] = F::mfma(ft[kk & 1][dt], dsf[kk], dq[dt]);
+          if (kk + 2 < NKK) load_tgroup(kk + 2);
+          sched_fence();
+        }
+      }
+      if (j + 1 < nt) {
+        tile_r2s_swz<D, C::BN>(smem + (buf ^ 1) * C::STAGE, tid, kreg);
+        tile_r2s_swz<D, C::BN>(smem + (buf ^ 1) * C::STAGE + C::TILE, tid, vreg);
+      }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) off.row[ks] ^= C::STAGE;
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) off.tr[h][dt] ^= C::STAGE;
+      __syncthreads();
+    }
+
+    SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
+    store_transposed<T, D, C::OSTR>(dq, scale, ob, dQ + head_off, q0, N, lane);
   }  // rep
 }
 

@@ -19,9 +19,17 @@
 //   * K/V tiles are double-buffered in LDS; the global loads of tile j+1 are issued before the
 //     arithmetic of tile j and written to the other buffer afterwards: one barrier per tile.
 //   * Row strides in LDS are padded (K: +16 B, V: +64 B) so the 16-byte row reads of K and
-//     the 4-row transposing reads of V spread over all banks.
+//     the 4-row transposing reads of V spread over all banks (measured: conflict cycles are
+//     1.5 % of LDS-active cycles).
+//   * Each 64-key tile runs as two 32-key online-softmax steps whose VALU work is interleaved,
+//     in program order, with the MFMAs of the other half (a wave issues in order); LDS operand
+//     reads are issued several MFMAs ahead and pinned there with scheduler fences.
+//   * Causal: the loop ends at the diagonal, only diagonal tiles are masked, waves skip tiles
+//     wholly above their rows, and a workgroup takes the complementary pair of query tiles
+//     (nqt-1-p, p) so every workgroup carries the same amount of work.
 #pragma once
 #include "mma_gfx950.hpp"
+#include "tiles_gfx950.hpp"
 
 namespace spark {
 
@@ -37,23 +45,6 @@ template <int D> struct FwdCfg {
   static constexpr int SMEM = 2 * STAGE;
   static_assert(4 * 32 * OSTR <= SMEM, "epilogue staging must fit in the K/V buffers");
 };
-
-// Workgroups are handed to the 8 XCDs round-robin by linear id.  Map the id so that each XCD
-// gets one contiguous range of logical work items: the query tiles of one head then share
-// that XCD's L2 for K and V.
-static __device__ __forceinline__ int xcd_contiguous(int id, int total) {
-  const int per = total >> 3, rem = total & 7;
-  const int xcd = id & 7, slot = id >> 3;
-  const int base = xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per;
-  return base + slot;
-}
-
-// Work items per head for a kernel that walks `tiles` tiles: causal kernels pair tile p with
-// tile tiles-1-p.
-template <bool CAUSAL>
-static __host__ __device__ __forceinline__ int causal_items(int tiles) {
-  return CAUSAL ? (tiles + 1) / 2 : tiles;
-}
 
 template <typename T, int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
@@ -88,256 +79,256 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
   const T* Vh = V + head_off;
 
   for (int rep = 0; rep < (CAUSAL ? 2 : 1); ++rep) {
-  const int qt = CAUSAL ? (rep == 0 ? nqt - 1 - item : item) : item;
-  if (CAUSAL && rep == 1) {
-    if (qt == nqt - 1 - item) break;  // odd tile count: the middle tile has no partner
-    __syncthreads();                  // the first tile's epilogue is done with the LDS
-  }
-
-  const int q0 = qt * C::BM + wave * 32;  // first query row of this wave
-  const int qrow = q0 + c32;              // this lane's query row
-  const int qrow_c = qrow < N ? qrow : N - 1;
-
-  v8 qf[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks)
-    qf[ks] = *reinterpret_cast<const v8*>(Qh + (size_t)qrow_c * D + ks * 16 + g * 8);
-
-  int kv_end = N;
-  if (CAUSAL) {
-    const int lim = (qt + 1) * C::BM;
-    kv_end = lim < N ? lim : N;
-  }
-  const int nt = (kv_end + C::BN - 1) / C::BN;
-
-  // Tile loads: thread t owns 16-byte chunk t of each group of 256 chunks (= 4096 bytes).
-  const BufView kview(Kh, (uint32_t)N * D * 2), vview(Vh, (uint32_t)N * D * 2);
-  u32x4 kreg[NLD], vreg[NLD];
-  auto load_tile = [&](int j) {
-    const uint32_t tile_off = (uint32_t)j * (C::BN * D * 2);
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      kreg[i] = kview.load16(tid * 16 + i * 4096, tile_off);
-      vreg[i] = vview.load16(tid * 16 + i * 4096, tile_off);
+    const int qt = CAUSAL ? (rep == 0 ? nqt - 1 - item : item) : item;
+    if (CAUSAL && rep == 1) {
+      if (qt == nqt - 1 - item) break;  // odd tile count: the middle tile has no partner
+      __syncthreads();                  // the first tile's epilogue is done with the LDS
     }
-  };
-  auto store_tile = [&](int buf) {
+
+    const int q0 = qt * C::BM + wave * 32;  // first query row of this wave
+    const int qrow = q0 + c32;              // this lane's query row
+    const int qrow_c = qrow < N ? qrow : N - 1;
+
+    v8 qf[KS];
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int c = tid + 256 * i;
-      const int row = c / CPR, cc = c % CPR;
-      lds_write(smem, buf * C::STAGE + row * C::KSTR + cc * 16, kreg[i]);
-      lds_write(smem, buf * C::STAGE + C::KBYTES + row * C::VSTR + cc * 16, vreg[i]);
+    for (int ks = 0; ks < KS; ++ks)
+      qf[ks] = *reinterpret_cast<const v8*>(Qh + (size_t)qrow_c * D + ks * 16 + g * 8);
+
+    int kv_end = N;
+    if (CAUSAL) {
+      const int lim = (qt + 1) * C::BM;
+      kv_end = lim < N ? lim : N;
     }
-  };
+    const int nt = (kv_end + C::BN - 1) / C::BN;
 
-  f32x16 o[DT];
+    // Tile loads: thread t owns 16-byte chunk t of each group of 256 chunks (= 4096 bytes).
+    const BufView kview(Kh, (uint32_t)N * D * 2), vview(Vh, (uint32_t)N * D * 2);
+    u32x4 kreg[NLD], vreg[NLD];
+    auto load_tile = [&](int j) {
+      const uint32_t tile_off = (uint32_t)j * (C::BN * D * 2);
 #pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
+      for (int i = 0; i < NLD; ++i) {
+        kreg[i] = kview.load16(tid * 16 + i * 4096, tile_off);
+        vreg[i] = vview.load16(tid * 16 + i * 4096, tile_off);
+      }
+    };
+    auto store_tile = [&](int buf) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
-  float m_run = -INFINITY;  // running row max (log2 domain)
-  float l_run = 0.f;        // running row sum over this lane's keys only (halves merged at the end)
+      for (int i = 0; i < NLD; ++i) {
+        const int c = tid + 256 * i;
+        const int row = c / CPR, cc = c % CPR;
+        lds_write(smem, buf * C::STAGE + row * C::KSTR + cc * 16, kreg[i]);
+        lds_write(smem, buf * C::STAGE + C::KBYTES + row * C::VSTR + cc * 16, vreg[i]);
+      }
+    };
 
-  load_tile(0);
-  // The Q fragments must have arrived before the loop: otherwise the waits for them would sit
-  // inside the loop body and would also wait for the next tile's prefetch every iteration.
-  wait_vmem_all();
+    f32x16 o[DT];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]));
-  store_tile(0);
-  __syncthreads();
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
+    float m_run = -INFINITY;  // running row max (log2 domain)
+    float l_run = 0.f;        // running row sum over this lane's keys only (halves merged at the end)
 
-  for (int j = 0; j < nt; ++j) {
-    const int buf = j & 1;
-    if (j + 1 < nt) load_tile(j + 1);
+    load_tile(0);
+    // The Q fragments must have arrived before the loop: otherwise the waits for them would sit
+    // inside the loop body and would also wait for the next tile's prefetch every iteration.
+    wait_vmem_all();
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]));
+    store_tile(0);
+    __syncthreads();
 
-    const int k0 = j * C::BN;
-    if (!CAUSAL || k0 <= q0 + 31) {  // wave-uniform: skip tiles entirely above the diagonal
-      SPARK_LDS const char* kb = smem + buf * C::STAGE;
-      SPARK_LDS const char* vb = kb + C::KBYTES;
+    for (int j = 0; j < nt; ++j) {
+      const int buf = j & 1;
+      if (j + 1 < nt) load_tile(j + 1);
 
-      // The 64-key tile is processed as two 32-key halves, each its own online-softmax step,
-      // so that the VALU work of one half sits between the MFMAs of the other:
-      //   S_0                   (MFMA)
-      //   S_1       ||  softmax of half 0   (an MFMA, then a few VALU instructions, ...)
-      //   O += P_0 V_0  ||  softmax of half 1
-      //   O += P_1 V_1
-      // A wave issues in order, so the VALU instructions must be placed between the MFMAs in
-      // program order; the fences keep the scheduler from regrouping them.  K fragments are read
-      // 8 reads ahead, V^T fragments one 16-key step ahead.
-      f32x16 s[2];
+      const int k0 = j * C::BN;
+      if (!CAUSAL || k0 <= q0 + 31) {  // wave-uniform: skip tiles entirely above the diagonal
+        SPARK_LDS const char* kb = smem + buf * C::STAGE;
+        SPARK_LDS const char* vb = kb + C::KBYTES;
+
+        // The 64-key tile is processed as two 32-key halves, each its own online-softmax step,
+        // so that the VALU work of one half sits between the MFMAs of the other:
+        //   S_0                   (MFMA)
+        //   S_1       ||  softmax of half 0   (an MFMA, then a few VALU instructions, ...)
+        //   O += P_0 V_0  ||  softmax of half 1
+        //   O += P_1 V_1
+        // A wave issues in order, so the VALU instructions must be placed between the MFMAs in
+        // program order; the fences keep the scheduler from regrouping them.  K fragments are read
+        // 8 reads ahead, V^T fragments one 16-key step ahead.
+        f32x16 s[2];
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
+        for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[mt][r] = 0.f;
-      constexpr int GPH = KS / 4;  // groups of 4 k-steps per half
-      v8 kf[2][4];
-      auto load_kgroup = [&](int gi) {  // gi = half * GPH + group
-        const int half = gi / GPH, ks0 = 4 * (gi % GPH);
+          for (int r = 0; r < 16; ++r) s[mt][r] = 0.f;
+        constexpr int GPH = KS / 4;  // groups of 4 k-steps per half
+        v8 kf[2][4];
+        auto load_kgroup = [&](int gi) {  // gi = half * GPH + group
+          const int half = gi / GPH, ks0 = 4 * (gi % GPH);
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-          kf[gi & 1][e] = lds_read16<v8>(kb, (half * 32 + c32) * C::KSTR + (ks0 + e) * 32 + g * 16);
-      };
-      v8 vf[2][DT];
-      auto load_vgroup = [&](int kk) {
-        const int row0 = 16 * kk + 4 * g + (i16 >> 2);
+          for (int e = 0; e < 4; ++e)
+            kf[gi & 1][e] = lds_read16<v8>(kb, (half * 32 + c32) * C::KSTR + (ks0 + e) * 32 + g * 16);
+        };
+        v8 vf[2][DT];
+        auto load_vgroup = [&](int kk) {
+          const int row0 = 16 * kk + 4 * g + (i16 >> 2);
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          const int col = dt * 32 + (c32 & 16) + 4 * (i16 & 3);
-          const v4 lo = lds_read_tr8<v4>(vb, row0 * C::VSTR + col * 2);
-          const v4 hi = lds_read_tr8<v4>(vb, (row0 + 8) * C::VSTR + col * 2);
-          vf[kk & 1][dt] = join4<v8, v4>(lo, hi);
+          for (int dt = 0; dt < DT; ++dt) {
+            const int col = dt * 32 + (c32 & 16) + 4 * (i16 & 3);
+            const v4 lo = lds_read_tr8<v4>(vb, row0 * C::VSTR + col * 2);
+            const v4 hi = lds_read_tr8<v4>(vb, (row0 + 8) * C::VSTR + col * 2);
+            vf[kk & 1][dt] = join4<v8, v4>(lo, hi);
+          }
+        };
+
+        const bool need_mask = (CAUSAL && k0 + C::BN - 1 > q0) || (k0 + C::BN > N);
+        float t[32];
+        // raw scores of one half -> t, masked; returns the scaled row maximum of the half
+        auto half_max = [&](int h) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) t[h * 16 + r] = s[h][r];
+          if (need_mask) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int key = k0 + h * 32 + 8 * (r / 4) + 4 * g + (r % 4);
+              const bool ok = key < N && (!CAUSAL || key <= qrow);
+              if (!ok) t[h * 16 + r] = -INFINITY;
+            }
+          }
+          float mx = t[h * 16];
+#pragma unroll
+          for (int r = 1; r < 16; ++r) mx = fmaxf(mx, t[h * 16 + r]);
+          return half_pair_max(mx) * scale_log2;  // scale > 0 commutes with the maximum
+        };
+        float rs = 0.f;
+        auto exp_elem = [&](int i) {
+          t[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(t[i], scale_log2, -m_run));
+          rs += t[i];
+        };
+
+        // ---- S_0 ----
+        load_kgroup(0);
+        load_kgroup(1);
+        sched_fence();
+#pragma unroll
+        for (int gi = 0; gi < GPH; ++gi) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) s[0] = F::mfma(kf[gi & 1][e], qf[4 * gi + e], s[0]);
+          if (gi + 2 < 2 * GPH) load_kgroup(gi + 2);
+          sched_fence();
         }
-      };
+        load_vgroup(0);
+        sched_fence();
 
-      const bool need_mask = (CAUSAL && k0 + C::BN - 1 > q0) || (k0 + C::BN > N);
-      float t[32];
-      // raw scores of one half -> t, masked; returns the scaled row maximum of the half
-      auto half_max = [&](int h) {
+        // Online softmax (Eq. 3) with a lazy reference point: m_run is only moved, and the
+        // accumulators only rescaled by exp(m_pre - m_cur), when some row's maximum grew by more
+        // than 2^8.  Until then P is formed against the old reference and stays <= 256, which fp32
+        // sums and the 16-bit MFMA operand hold without loss; the final O = acc / l and
+        // LSE = m + log l do not depend on which reference was used.
+        {
+          const float mx = half_max(0);
+          if (__any(mx > m_run + 8.0f)) {
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            m_run = m_new;
+            l_run *= alpha;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) t[h * 16 + r] = s[h][r];
-        if (need_mask) {
+            for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = k0 + h * 32 + 8 * (r / 4) + 4 * g + (r % 4);
-            const bool ok = key < N && (!CAUSAL || key <= qrow);
-            if (!ok) t[h * 16 + r] = -INFINITY;
+              for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
           }
         }
-        float mx = t[h * 16];
+        // ---- S_1  ||  exponentials of half 0 ----
+        constexpr int EPU = 16 / KS;  // elements per MFMA
 #pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, t[h * 16 + r]);
-        return half_pair_max(mx) * scale_log2;  // scale > 0 commutes with the maximum
-      };
-      float rs = 0.f;
-      auto exp_elem = [&](int i) {
-        t[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(t[i], scale_log2, -m_run));
-        rs += t[i];
-      };
-
-      // ---- S_0 ----
-      load_kgroup(0);
-      load_kgroup(1);
-      sched_fence();
+        for (int gi = GPH; gi < 2 * GPH; ++gi) {
 #pragma unroll
-      for (int gi = 0; gi < GPH; ++gi) {
+          for (int e = 0; e < 4; ++e) {
+            s[1] = F::mfma(kf[gi & 1][e], qf[4 * (gi - GPH) + e], s[1]);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) s[0] = F::mfma(kf[gi & 1][e], qf[4 * gi + e], s[0]);
-        if (gi + 2 < 2 * GPH) load_kgroup(gi + 2);
-        sched_fence();
-      }
-      load_vgroup(0);
-      sched_fence();
-
-      // Online softmax (Eq. 3) with a lazy reference point: m_run is only moved, and the
-      // accumulators only rescaled by exp(m_pre - m_cur), when some row's maximum grew by more
-      // than 2^8.  Until then P is formed against the old reference and stays <= 256, which fp32
-      // sums and the 16-bit MFMA operand hold without loss; the final O = acc / l and
-      // LSE = m + log l do not depend on which reference was used.
-      {
-        const float mx = half_max(0);
-        if (__any(mx > m_run + 8.0f)) {
-          const float m_new = fmaxf(m_run, mx);
-          const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-          m_run = m_new;
-          l_run *= alpha;
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
-        }
-      }
-      // ---- S_1  ||  exponentials of half 0 ----
-      constexpr int EPU = 16 / KS;  // elements per MFMA
-#pragma unroll
-      for (int gi = GPH; gi < 2 * GPH; ++gi) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          s[1] = F::mfma(kf[gi & 1][e], qf[4 * (gi - GPH) + e], s[1]);
-#pragma unroll
-          for (int x = 0; x < EPU; ++x) exp_elem(((gi - GPH) * 4 + e) * EPU + x);
+            for (int x = 0; x < EPU; ++x) exp_elem(((gi - GPH) * 4 + e) * EPU + x);
+            sched_fence();
+          }
+          if (gi + 2 < 2 * GPH) load_kgroup(gi + 2);
+          if (gi == GPH) load_vgroup(1);
           sched_fence();
         }
-        if (gi + 2 < 2 * GPH) load_kgroup(gi + 2);
-        if (gi == GPH) load_vgroup(1);
-        sched_fence();
-      }
-      // ---- boundary: reference check of half 1 (rarely moves; then P_0 is rescaled too) ----
-      {
-        const float mx = half_max(1);
-        if (__any(mx > m_run + 8.0f)) {
-          const float m_new = fmaxf(m_run, mx);
-          const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-          m_run = m_new;
-          l_run *= alpha;
-          rs *= alpha;
+        // ---- boundary: reference check of half 1 (rarely moves; then P_0 is rescaled too) ----
+        {
+          const float mx = half_max(1);
+          if (__any(mx > m_run + 8.0f)) {
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            m_run = m_new;
+            l_run *= alpha;
+            rs *= alpha;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) t[i] *= alpha;
+            for (int i = 0; i < 16; ++i) t[i] *= alpha;
 #pragma unroll
-          for (int dt = 0; dt < DT; ++dt)
+            for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+              for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+          }
         }
-      }
-      v8 pf[4];
-      pf[0] = pack8<T>(&t[0]);
-      pf[1] = pack8<T>(&t[8]);
-      sched_fence();
-      // ---- O^T += V_0^T P_0^T  ||  exponentials of half 1 ----
-      constexpr int EPV = 16 / (2 * DT);  // elements per MFMA
+        v8 pf[4];
+        pf[0] = pack8<T>(&t[0]);
+        pf[1] = pack8<T>(&t[8]);
+        sched_fence();
+        // ---- O^T += V_0^T P_0^T  ||  exponentials of half 1 ----
+        constexpr int EPV = 16 / (2 * DT);  // elements per MFMA
 #pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
+        for (int kk = 0; kk < 2; ++kk) {
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          o[dt] = F::mfma(vf[kk & 1][dt], pf[kk], o[dt]);
+          for (int dt = 0; dt < DT; ++dt) {
+            o[dt] = F::mfma(vf[kk & 1][dt], pf[kk], o[dt]);
 #pragma unroll
-          for (int x = 0; x < EPV; ++x) exp_elem(16 + (kk * DT + dt) * EPV + x);
+            for (int x = 0; x < EPV; ++x) exp_elem(16 + (kk * DT + dt) * EPV + x);
+            sched_fence();
+          }
+          load_vgroup(kk + 2);
           sched_fence();
         }
-        load_vgroup(kk + 2);
+        l_run += rs;
+        pf[2] = pack8<T>(&t[16]);
+        pf[3] = pack8<T>(&t[24]);
         sched_fence();
-      }
-      l_run += rs;
-      pf[2] = pack8<T>(&t[16]);
-      pf[3] = pack8<T>(&t[24]);
-      sched_fence();
-      // ---- O^T += V_1^T P_1^T ----
+        // ---- O^T += V_1^T P_1^T ----
 #pragma unroll
-      for (int kk = 2; kk < 4; ++kk) {
+        for (int kk = 2; kk < 4; ++kk) {
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) o[dt] = F::mfma(vf[kk & 1][dt], pf[kk], o[dt]);
-        sched_fence();
+          for (int dt = 0; dt < DT; ++dt) o[dt] = F::mfma(vf[kk & 1][dt], pf[kk], o[dt]);
+          sched_fence();
+        }
       }
+
+      if (j + 1 < nt) store_tile(buf ^ 1);
+      __syncthreads();
     }
 
-    if (j + 1 < nt) store_tile(buf ^ 1);
-    __syncthreads();
-  }
-
-  // Epilogue: normalise, round once, transpose through this wave's LDS slice, store rows.
-  l_run = half_pair_sum(l_run);
-  const float inv = 1.0f / l_run;
-  SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
+    // Epilogue: normalise, round once, transpose through this wave's LDS slice, store rows.
+    l_run = half_pair_sum(l_run);
+    const float inv = 1.0f / l_run;
+    SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
 #pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-    for (int r4 = 0; r4 < 4; ++r4) {
-      v4 pk;
+      for (int r4 = 0; r4 < 4; ++r4) {
+        v4 pk;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) pk[e] = (T)(o[dt][r4 * 4 + e] * inv);
-      lds_write(ob, c32 * C::OSTR + (dt * 32 + 8 * r4 + 4 * g) * 2, pk);
+        for (int e = 0; e < 4; ++e) pk[e] = (T)(o[dt][r4 * 4 + e] * inv);
+        lds_write(ob, c32 * C::OSTR + (dt * 32 + 8 * r4 + 4 * g) * 2, pk);
+      }
+    T* Oh = O + head_off;
+    constexpr int RPP = 64 / CPR;  // rows per pass of the wave
+#pragma unroll
+    for (int p = 0; p < 32 / RPP; ++p) {
+      const int row = p * RPP + lane / CPR, cc = lane % CPR;
+      const u32x4 v = lds_read16<u32x4>(ob, row * C::OSTR + cc * 16);
+      if (q0 + row < N) *reinterpret_cast<u32x4*>(Oh + (size_t)(q0 + row) * D + cc * 8) = v;
     }
-  T* Oh = O + head_off;
-  constexpr int RPP = 64 / CPR;  // rows per pass of the wave
-#pragma unroll
-  for (int p = 0; p < 32 / RPP; ++p) {
-    const int row = p * RPP + lane / CPR, cc = lane % CPR;
-    const u32x4 v = lds_read16<u32x4>(ob, row * C::OSTR + cc * 16);
-    if (q0 + row < N) *reinterpret_cast<u32x4*>(Oh + (size_t)(q0 + row) * D + cc * 8) = v;
-  }
-  if (g == 0 && qrow < N)
-    LSE[(size_t)head * N + qrow] = (m_run + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f;
+    if (g == 0 && qrow < N)
+      LSE[(size_t)head * N + qrow] = (m_run + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f;
   }  // rep
 }
 
