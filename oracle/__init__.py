@@ -4,8 +4,11 @@ Nothing in the product package imports this; it is loaded by the tests, by the
 smoke check and by the benchmark's cpu_baseline leg.
 """
 from .mha_oracle import (  # noqa: F401
+    OracleLib,
     build,
-    num_threads,
-    mha_fwd,
+    compile_source,
+    default,
     mha_bwd,
+    mha_fwd,
+    num_threads,
 )

@@ -20,41 +20,25 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "mha_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle_mha.so")
-_lib = None
+_default = None
 
 _dp = ctypes.POINTER(ctypes.c_double)
+GCC_FLAGS = ["-O3", "-mavx2", "-mfma", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra"]
+
+
+def compile_source(src: str, out: str) -> str:
+    """gcc one C source into a shared library (plain -O3, AVX2; no fast-math)."""
+    tmp = out + ".tmp.%d" % os.getpid()
+    subprocess.run(["gcc"] + GCC_FLAGS + ["-o", tmp, src, "-lm"], check=True)
+    os.replace(tmp, out)
+    return out
 
 
 def build(force: bool = False) -> str:
-    """Compile the C oracle with gcc (plain -O3, AVX2; no fast-math)."""
+    """Compile the C oracle next to its source if it is missing or stale."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        tmp = _LIB + ".tmp.%d" % os.getpid()
-        cmd = ["gcc", "-O3", "-mavx2", "-mfma", "-fopenmp", "-fPIC", "-shared", "-std=c11",
-               "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"]
-        subprocess.run(cmd, check=True)
-        os.replace(tmp, _LIB)
+        compile_source(_SRC, _LIB)
     return _LIB
-
-
-def _load():
-    global _lib
-    if _lib is None:
-        build()
-        lib = ctypes.CDLL(_LIB)
-        lib.oracle_num_threads.restype = ctypes.c_int
-        lib.oracle_mha_fwd.restype = ctypes.c_int
-        lib.oracle_mha_fwd.argtypes = [_dp, _dp, _dp, _dp, _dp, _dp, ctypes.c_int, ctypes.c_int,
-                                       ctypes.c_int, ctypes.c_double, ctypes.c_int]
-        lib.oracle_mha_bwd.restype = ctypes.c_int
-        lib.oracle_mha_bwd.argtypes = [_dp] * 10 + [ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                                    ctypes.c_double, ctypes.c_int]
-        _lib = lib
-    return _lib
-
-
-def num_threads() -> int:
-    """OpenMP threads the oracle will use."""
-    return int(_load().oracle_num_threads())
 
 
 def _chk(*arrs):
@@ -73,29 +57,66 @@ def _p(a):
     return a.ctypes.data_as(_dp) if a is not None else None
 
 
+class OracleLib:
+    """The oracle's entry points bound to one shared library (the default build, or a
+    library a test compiled itself, e.g. from a deliberately broken copy of the source)."""
+
+    def __init__(self, path: str):
+        lib = ctypes.CDLL(path)
+        lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_mha_fwd.restype = ctypes.c_int
+        lib.oracle_mha_fwd.argtypes = [_dp, _dp, _dp, _dp, _dp, _dp, ctypes.c_int, ctypes.c_int,
+                                       ctypes.c_int, ctypes.c_double, ctypes.c_int]
+        lib.oracle_mha_bwd.restype = ctypes.c_int
+        lib.oracle_mha_bwd.argtypes = [_dp] * 10 + [ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                    ctypes.c_double, ctypes.c_int]
+        self._lib = lib
+
+    def num_threads(self) -> int:
+        """OpenMP threads the oracle will use."""
+        return int(self._lib.oracle_num_threads())
+
+    def mha_fwd(self, Q, K, V, scale: float, causal: bool, return_P: bool = False):
+        """O [B,H,N,d], LSE [B,H,N] (and P [B,H,N,N] if asked) in float64."""
+        Q, K, V = _chk(Q, K, V)
+        B, H, N, d = Q.shape
+        O = np.empty_like(Q)
+        LSE = np.empty((B, H, N), dtype=np.float64)
+        P = np.empty((B, H, N, N), dtype=np.float64) if return_P else None
+        rc = self._lib.oracle_mha_fwd(_p(Q), _p(K), _p(V), _p(O), _p(LSE), _p(P), B * H, N, d,
+                                      float(scale), int(bool(causal)))
+        if rc != 0:
+            raise RuntimeError("oracle_mha_fwd failed (%d)" % rc)
+        return (O, LSE, P) if return_P else (O, LSE)
+
+    def mha_bwd(self, Q, K, V, dO, scale: float, causal: bool):
+        """dict with dQ, dK, dV [B,H,N,d], and the oracle's own O, LSE, D."""
+        Q, K, V, dO = _chk(Q, K, V, dO)
+        B, H, N, d = Q.shape
+        dQ, dK, dV, O = (np.empty_like(Q) for _ in range(4))
+        LSE = np.empty((B, H, N), dtype=np.float64)
+        D = np.empty((B, H, N), dtype=np.float64)
+        rc = self._lib.oracle_mha_bwd(_p(Q), _p(K), _p(V), _p(dO), _p(dQ), _p(dK), _p(dV), _p(O),
+                                      _p(LSE), _p(D), B * H, N, d, float(scale), int(bool(causal)))
+        if rc != 0:
+            raise RuntimeError("oracle_mha_bwd failed (%d)" % rc)
+        return {"dQ": dQ, "dK": dK, "dV": dV, "O": O, "LSE": LSE, "D": D}
+
+
+def default() -> OracleLib:
+    global _default
+    if _default is None:
+        _default = OracleLib(build())
+    return _default
+
+
+def num_threads() -> int:
+    return default().num_threads()
+
+
 def mha_fwd(Q, K, V, scale: float, causal: bool, return_P: bool = False):
-    """O [B,H,N,d], LSE [B,H,N] (and P [B,H,N,N] if asked) in float64."""
-    Q, K, V = _chk(Q, K, V)
-    B, H, N, d = Q.shape
-    O = np.empty_like(Q)
-    LSE = np.empty((B, H, N), dtype=np.float64)
-    P = np.empty((B, H, N, N), dtype=np.float64) if return_P else None
-    rc = _load().oracle_mha_fwd(_p(Q), _p(K), _p(V), _p(O), _p(LSE), _p(P), B * H, N, d,
-                                float(scale), int(bool(causal)))
-    if rc != 0:
-        raise RuntimeError("oracle_mha_fwd failed (%d)" % rc)
-    return (O, LSE, P) if return_P else (O, LSE)
+    return default().mha_fwd(Q, K, V, scale, causal, return_P)
 
 
 def mha_bwd(Q, K, V, dO, scale: float, causal: bool):
-    """dict with dQ, dK, dV [B,H,N,d], and the oracle's own O, LSE, D."""
-    Q, K, V, dO = _chk(Q, K, V, dO)
-    B, H, N, d = Q.shape
-    dQ, dK, dV, O = (np.empty_like(Q) for _ in range(4))
-    LSE = np.empty((B, H, N), dtype=np.float64)
-    D = np.empty((B, H, N), dtype=np.float64)
-    rc = _load().oracle_mha_bwd(_p(Q), _p(K), _p(V), _p(dO), _p(dQ), _p(dK), _p(dV), _p(O),
-                                _p(LSE), _p(D), B * H, N, d, float(scale), int(bool(causal)))
-    if rc != 0:
-        raise RuntimeError("oracle_mha_bwd failed (%d)" % rc)
-    return {"dQ": dQ, "dK": dK, "dV": dV, "O": O, "LSE": LSE, "D": D}
+    return default().mha_bwd(Q, K, V, dO, scale, causal)
