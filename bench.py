@@ -124,6 +124,10 @@ def main():
     ap.add_argument("--workload", default="C4", help="C1..C5 (default C4: N=4096, d=128, bf16, causal)")
     ap.add_argument("--all", action="store_true", help="also time the other four configs (extra field)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time the paper's own grid (Sec. 4.1: hidden 2048, d in {64,128}, "
+                         "N in {512..16384}, B = 16384/N, both mask settings, fp16, no dropout) "
+                         "and add it as an extra field")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run 5 plain device copies of 256 MiB (reads 256 MiB, writes 256 MiB each) "
                          "so FETCH_SIZE / WRITE_SIZE counters can be scaled against a known size")
@@ -184,6 +188,19 @@ def main():
                             "bwd_tflops": ww.bwd_flops / ((k2["bwd_dot"] + k2["bwd_dkdv"] + k2["bwd_dq"]) * 1e-3) / 1e12,
                             "kernel_ms": k2}
         out["other_configs"] = others
+    if args.sweep:
+        sweep = []
+        for d in (64, 128):
+            for N in (512, 1024, 2048, 4096, 16384):
+                for causal in (False, True):
+                    ww = synth.Workload("S", 16384 // N, 2048 // d, N, d, synth.F16, causal, 1.0, 2000 + N + d)
+                    m2, k2 = time_workload(ww, max(5, args.steps // 3), 2)
+                    bwd_ms = k2["bwd_dot"] + k2["bwd_dkdv"] + k2["bwd_dq"]
+                    sweep.append({"d": d, "N": N, "B": ww.B, "H": ww.H, "causal": causal,
+                                  "fwd_tflops": ww.fwd_flops / (k2["fwd"] * 1e-3) / 1e12,
+                                  "bwd_tflops": ww.bwd_flops / (bwd_ms * 1e-3) / 1e12,
+                                  "tflops": (ww.fwd_flops + ww.bwd_flops) / (m2 * 1e-3) / 1e12})
+        out["paper_sweep"] = sweep
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out), flush=True)

@@ -88,3 +88,17 @@ def test_bitwise_reproducible():
     b = pu.run_gpu(inp, w.dtype, w.scale, True)
     for n in ("O", "LSE", "dQ", "dK", "dV"):
         assert torch.equal(a[n], b[n]), n
+
+
+@pytest.mark.parametrize("d,causal", [(64, True), (128, False)])
+def test_paper_sweep_longest_sequence_sampled(d, causal):
+    """The longest point of the paper's own grid (Sec. 4.1): N = 16384, B = 1, H = 2048/d, fp16.
+    Full-size GPU run; the oracle checks one (batch, head) element by element."""
+    N, B, H = 16384, 1, 2048 // d
+    inp = synth.make_inputs(B, H, N, d, synth.F16, seed=16384 + d)
+    gpu = pu.run_gpu(inp, synth.F16, 1.0 / math.sqrt(d), causal)
+    heads = [H - 1]
+    ref = pu.run_oracle(inp, synth.F16, 1.0 / math.sqrt(d), causal, heads=heads)
+    m = pu.compare(gpu, ref, synth.F16, heads=heads)
+    print(f"\n[parity] sweep N={N} d={d} causal={causal} head={heads}: {m}", flush=True)
+    pu.assert_within_tolerance(m, ("sweep", d, causal))
