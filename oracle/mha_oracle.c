@@ -6,8 +6,11 @@
  * with the GPU path, and the GPU path never calls it.  Only the tests, the
  * smoke check and the benchmark's cpu_baseline leg may load it.
  *
- * What it computes, per (batch, head) independently, for row-major N x d
- * matrices Q, K, V (paper Sec. 2.1, Eq. 1, with the scale applied to the logits
+ * What it computes, per (batch, head) independently, for row-major matrices
+ * Q (Nq x d) and K, V (Nk x d).  Self-attention has Nq = Nk = N; the decoder's
+ * second attention layer of Sec. 2.1 takes its queries from one sequence and its
+ * keys and values from another, so the two lengths differ there.  The causal
+ * mask is defined for Nq = Nk only.  (Paper Sec. 2.1, Eq. 1, with the scale applied to the logits
  * before the softmax, which is the only reading under which rows of P sum to
  * one and which every system the paper compares against computes):
  *
@@ -33,7 +36,7 @@
  *   dK_jk  = scale * sum_i dS_ij Q_ik   (dK = dS^T Q; the printed "Q dS^T" has
  *                                        no consistent shape)
  *
- * The N x N matrices are materialised per head.  There is no tiling, no online
+ * The Nq x Nk matrices are materialised per head.  There is no tiling, no online
  * softmax, no fusion: a reader can check every loop against the formulas above.
  * OpenMP only spreads independent rows (or independent output rows) over
  * threads; it reorders no sum.
@@ -53,13 +56,13 @@ int oracle_num_threads(void) {
 #endif
 }
 
-/* S and P for one head.  P is N x N row-major; masked entries are exactly 0. */
-static void head_softmax(const double *Q, const double *K, int N, int d,
+/* S and P for one head.  P is Nq x Nk row-major; masked entries are exactly 0. */
+static void head_softmax(const double *Q, const double *K, int Nq, int Nk, int d,
                          double scale, int causal, double *P, double *LSE) {
 #pragma omp parallel for schedule(dynamic, 8)
-  for (int i = 0; i < N; ++i) {
-    double *Pi = P + (size_t)i * N;
-    const int jend = causal ? i + 1 : N;
+  for (int i = 0; i < Nq; ++i) {
+    double *Pi = P + (size_t)i * Nk;
+    const int jend = causal ? i + 1 : Nk;
     double m = -INFINITY;
     for (int j = 0; j < jend; ++j) {
       double s = 0.0;
@@ -74,19 +77,19 @@ static void head_softmax(const double *Q, const double *K, int N, int d,
       l += Pi[j];
     }
     for (int j = 0; j < jend; ++j) Pi[j] /= l;
-    for (int j = jend; j < N; ++j) Pi[j] = 0.0;
+    for (int j = jend; j < Nk; ++j) Pi[j] = 0.0;
     LSE[i] = m + log(l);
   }
 }
 
 /* O = P V for one head. */
-static void head_pv(const double *P, const double *V, int N, int d, double *O) {
+static void head_pv(const double *P, const double *V, int Nq, int Nk, int d, double *O) {
 #pragma omp parallel for schedule(dynamic, 8)
-  for (int i = 0; i < N; ++i) {
+  for (int i = 0; i < Nq; ++i) {
     double *Oi = O + (size_t)i * d;
     for (int k = 0; k < d; ++k) Oi[k] = 0.0;
-    for (int j = 0; j < N; ++j) {
-      const double p = P[(size_t)i * N + j];
+    for (int j = 0; j < Nk; ++j) {
+      const double p = P[(size_t)i * Nk + j];
       if (p == 0.0) continue; /* masked or underflowed: contributes exactly 0 */
       for (int k = 0; k < d; ++k) Oi[k] += p * V[(size_t)j * d + k];
     }
@@ -94,22 +97,25 @@ static void head_pv(const double *P, const double *V, int N, int d, double *O) {
 }
 
 /*
- * Forward for B*H heads.  Q, K, V: [B*H][N][d] fp64 (the caller widens the
- * 16-bit inputs exactly).  Outputs O [B*H][N][d], LSE [B*H][N].  P_out, if not
- * NULL, receives the full probability matrices [B*H][N][N] (tests only).
- * Returns 0, or -1 on allocation failure / bad arguments.
+ * Forward for B*H heads.  Q: [B*H][Nq][d], K, V: [B*H][Nk][d] fp64 (the caller
+ * widens the 16-bit inputs exactly).  Outputs O [B*H][Nq][d], LSE [B*H][Nq].
+ * P_out, if not NULL, receives the full probability matrices [B*H][Nq][Nk]
+ * (tests only).  Returns 0, or -1 on allocation failure / bad arguments
+ * (causal with Nq != Nk is a bad argument).
  */
 int oracle_mha_fwd(const double *Q, const double *K, const double *V, double *O,
-                   double *LSE, double *P_out, int BH, int N, int d,
+                   double *LSE, double *P_out, int BH, int Nq, int Nk, int d,
                    double scale, int causal) {
-  if (!Q || !K || !V || !O || !LSE || BH < 0 || N <= 0 || d <= 0) return -1;
-  double *Pbuf = P_out ? NULL : (double *)malloc((size_t)N * N * sizeof(double));
+  if (!Q || !K || !V || !O || !LSE || BH < 0 || Nq <= 0 || Nk <= 0 || d <= 0) return -1;
+  if (causal && Nq != Nk) return -1;
+  double *Pbuf = P_out ? NULL : (double *)malloc((size_t)Nq * Nk * sizeof(double));
   if (!P_out && !Pbuf) return -1;
   for (int h = 0; h < BH; ++h) {
-    const size_t off = (size_t)h * N * d;
-    double *P = P_out ? P_out + (size_t)h * N * N : Pbuf;
-    head_softmax(Q + off, K + off, N, d, scale, causal, P, LSE + (size_t)h * N);
-    head_pv(P, V + off, N, d, O + off);
+    const size_t offq = (size_t)h * Nq * d; /* Q, O */
+    const size_t offk = (size_t)h * Nk * d; /* K, V */
+    double *P = P_out ? P_out + (size_t)h * Nq * Nk : Pbuf;
+    head_softmax(Q + offq, K + offk, Nq, Nk, d, scale, causal, P, LSE + (size_t)h * Nq);
+    head_pv(P, V + offk, Nq, Nk, d, O + offq);
   }
   free(Pbuf);
   return 0;
@@ -117,61 +123,63 @@ int oracle_mha_fwd(const double *Q, const double *K, const double *V, double *O,
 
 /*
  * Backward for B*H heads.  Recomputes the forward in fp64 itself (its own O
- * feeds D), then applies Eq. 4.  Outputs dQ, dK, dV [B*H][N][d]; also returns
- * O and LSE if the pointers are not NULL, and D [B*H][N] if D_out is not NULL.
+ * feeds D), then applies Eq. 4.  dO, dQ (and O_out): [B*H][Nq][d]; dK, dV:
+ * [B*H][Nk][d]; LSE_out, D_out: [B*H][Nq]; the three *_out pointers may be NULL.
  */
 int oracle_mha_bwd(const double *Q, const double *K, const double *V,
                    const double *dO, double *dQ, double *dK, double *dV,
-                   double *O_out, double *LSE_out, double *D_out, int BH, int N,
-                   int d, double scale, int causal) {
-  if (!Q || !K || !V || !dO || !dQ || !dK || !dV || BH < 0 || N <= 0 || d <= 0)
+                   double *O_out, double *LSE_out, double *D_out, int BH, int Nq,
+                   int Nk, int d, double scale, int causal) {
+  if (!Q || !K || !V || !dO || !dQ || !dK || !dV || BH < 0 || Nq <= 0 || Nk <= 0 || d <= 0)
     return -1;
-  double *P = (double *)malloc((size_t)N * N * sizeof(double));
-  double *dS = (double *)malloc((size_t)N * N * sizeof(double));
-  double *O = (double *)malloc((size_t)N * d * sizeof(double));
-  double *LSE = (double *)malloc((size_t)N * sizeof(double));
-  double *D = (double *)malloc((size_t)N * sizeof(double));
+  if (causal && Nq != Nk) return -1;
+  double *P = (double *)malloc((size_t)Nq * Nk * sizeof(double));
+  double *dS = (double *)malloc((size_t)Nq * Nk * sizeof(double));
+  double *O = (double *)malloc((size_t)Nq * d * sizeof(double));
+  double *LSE = (double *)malloc((size_t)Nq * sizeof(double));
+  double *D = (double *)malloc((size_t)Nq * sizeof(double));
   if (!P || !dS || !O || !LSE || !D) {
     free(P); free(dS); free(O); free(LSE); free(D);
     return -1;
   }
   for (int h = 0; h < BH; ++h) {
-    const size_t off = (size_t)h * N * d;
-    const double *Qh = Q + off, *Kh = K + off, *Vh = V + off, *dOh = dO + off;
-    head_softmax(Qh, Kh, N, d, scale, causal, P, LSE);
-    head_pv(P, Vh, N, d, O);
+    const size_t offq = (size_t)h * Nq * d; /* Q, dO, dQ, O */
+    const size_t offk = (size_t)h * Nk * d; /* K, V, dK, dV */
+    const double *Qh = Q + offq, *Kh = K + offk, *Vh = V + offk, *dOh = dO + offq;
+    head_softmax(Qh, Kh, Nq, Nk, d, scale, causal, P, LSE);
+    head_pv(P, Vh, Nq, Nk, d, O);
     /* D_i, dP_ij, dS_ij: independent per query row i */
 #pragma omp parallel for schedule(dynamic, 8)
-    for (int i = 0; i < N; ++i) {
+    for (int i = 0; i < Nq; ++i) {
       double Di = 0.0;
       for (int k = 0; k < d; ++k) Di += dOh[(size_t)i * d + k] * O[(size_t)i * d + k];
       D[i] = Di;
-      const int jend = causal ? i + 1 : N;
+      const int jend = causal ? i + 1 : Nk;
       for (int j = 0; j < jend; ++j) {
         double dp = 0.0;
         for (int k = 0; k < d; ++k) dp += dOh[(size_t)i * d + k] * Vh[(size_t)j * d + k];
-        dS[(size_t)i * N + j] = P[(size_t)i * N + j] * (dp - Di);
+        dS[(size_t)i * Nk + j] = P[(size_t)i * Nk + j] * (dp - Di);
       }
-      for (int j = jend; j < N; ++j) dS[(size_t)i * N + j] = 0.0;
+      for (int j = jend; j < Nk; ++j) dS[(size_t)i * Nk + j] = 0.0;
       /* dQ_i = scale * sum_j dS_ij K_j */
-      double *dQi = dQ + off + (size_t)i * d;
+      double *dQi = dQ + offq + (size_t)i * d;
       for (int k = 0; k < d; ++k) dQi[k] = 0.0;
       for (int j = 0; j < jend; ++j) {
-        const double ds = dS[(size_t)i * N + j];
+        const double ds = dS[(size_t)i * Nk + j];
         for (int k = 0; k < d; ++k) dQi[k] += ds * Kh[(size_t)j * d + k];
       }
       for (int k = 0; k < d; ++k) dQi[k] *= scale;
     }
     /* dV_j = sum_i P_ij dO_i ;  dK_j = scale * sum_i dS_ij Q_i : independent per key row j */
 #pragma omp parallel for schedule(dynamic, 8)
-    for (int j = 0; j < N; ++j) {
-      double *dVj = dV + off + (size_t)j * d;
-      double *dKj = dK + off + (size_t)j * d;
+    for (int j = 0; j < Nk; ++j) {
+      double *dVj = dV + offk + (size_t)j * d;
+      double *dKj = dK + offk + (size_t)j * d;
       for (int k = 0; k < d; ++k) { dVj[k] = 0.0; dKj[k] = 0.0; }
       const int ibeg = causal ? j : 0;
-      for (int i = ibeg; i < N; ++i) {
-        const double p = P[(size_t)i * N + j];
-        const double ds = dS[(size_t)i * N + j];
+      for (int i = ibeg; i < Nq; ++i) {
+        const double p = P[(size_t)i * Nk + j];
+        const double ds = dS[(size_t)i * Nk + j];
         for (int k = 0; k < d; ++k) {
           dVj[k] += p * dOh[(size_t)i * d + k];
           dKj[k] += ds * Qh[(size_t)i * d + k];
@@ -179,9 +187,9 @@ int oracle_mha_bwd(const double *Q, const double *K, const double *V,
       }
       for (int k = 0; k < d; ++k) dKj[k] *= scale;
     }
-    if (O_out) for (size_t t = 0; t < (size_t)N * d; ++t) O_out[off + t] = O[t];
-    if (LSE_out) for (int i = 0; i < N; ++i) LSE_out[(size_t)h * N + i] = LSE[i];
-    if (D_out) for (int i = 0; i < N; ++i) D_out[(size_t)h * N + i] = D[i];
+    if (O_out) for (size_t t = 0; t < (size_t)Nq * d; ++t) O_out[offq + t] = O[t];
+    if (LSE_out) for (int i = 0; i < Nq; ++i) LSE_out[(size_t)h * Nq + i] = LSE[i];
+    if (D_out) for (int i = 0; i < Nq; ++i) D_out[(size_t)h * Nq + i] = D[i];
   }
   free(P); free(dS); free(O); free(LSE); free(D);
   return 0;

@@ -3,7 +3,9 @@
 TEST INFRASTRUCTURE ONLY: the HIP path never imports or calls this module, and
 this module imports nothing from the HIP package.  All arithmetic lives in the C
 file; this wrapper only checks shapes, widens nothing and converts nothing
-(inputs must already be float64 arrays of shape [B, H, N, d]).
+(inputs must already be float64 arrays: Q and dO of shape [B, H, Nq, d], K and V
+of shape [B, H, Nk, d]; self-attention has Nq = Nk, the cross-attention of the
+decoder's second attention layer in Sec. 2.1 does not).
 
 The definitions follow the paper's Eq. 1 (forward), Sec. 3.2.1 Eq. 2 (softmax,
 with l = sum of f) and Sec. 3.3 Eq. 4 (backward, dK = dS^T Q); see the header of
@@ -41,16 +43,19 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
-def _chk(*arrs):
-    shape = arrs[0].shape
-    if len(shape) != 4:
+def _chk(Q, K, V, dO=None):
+    """Shapes: Q (and dO) [B,H,Nq,d]; K, V [B,H,Nk,d]."""
+    if Q.ndim != 4 or K.ndim != 4:
         raise ValueError("expected [B, H, N, d] arrays")
-    out = []
+    if K.shape[:2] != Q.shape[:2] or K.shape[3] != Q.shape[3] or V.shape != K.shape:
+        raise ValueError("K, V must be [B, H, Nk, d] with Q's B, H, d")
+    if dO is not None and dO.shape != Q.shape:
+        raise ValueError("dO must have Q's shape")
+    arrs = [a for a in (Q, K, V, dO) if a is not None]
     for a in arrs:
-        if a.dtype != np.float64 or a.shape != shape:
-            raise ValueError("oracle inputs must be float64 arrays of one shape")
-        out.append(np.ascontiguousarray(a))
-    return out
+        if a.dtype != np.float64:
+            raise ValueError("oracle inputs must be float64 arrays")
+    return [np.ascontiguousarray(a) for a in arrs]
 
 
 def _p(a):
@@ -66,10 +71,10 @@ class OracleLib:
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_mha_fwd.restype = ctypes.c_int
         lib.oracle_mha_fwd.argtypes = [_dp, _dp, _dp, _dp, _dp, _dp, ctypes.c_int, ctypes.c_int,
-                                       ctypes.c_int, ctypes.c_double, ctypes.c_int]
+                                       ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_int]
         lib.oracle_mha_bwd.restype = ctypes.c_int
         lib.oracle_mha_bwd.argtypes = [_dp] * 10 + [ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                                    ctypes.c_double, ctypes.c_int]
+                                                    ctypes.c_int, ctypes.c_double, ctypes.c_int]
         self._lib = lib
 
     def num_threads(self) -> int:
@@ -77,27 +82,31 @@ class OracleLib:
         return int(self._lib.oracle_num_threads())
 
     def mha_fwd(self, Q, K, V, scale: float, causal: bool, return_P: bool = False):
-        """O [B,H,N,d], LSE [B,H,N] (and P [B,H,N,N] if asked) in float64."""
+        """O [B,H,Nq,d], LSE [B,H,Nq] (and P [B,H,Nq,Nk] if asked) in float64."""
         Q, K, V = _chk(Q, K, V)
-        B, H, N, d = Q.shape
+        B, H, Nq, d = Q.shape
+        Nk = K.shape[2]
         O = np.empty_like(Q)
-        LSE = np.empty((B, H, N), dtype=np.float64)
-        P = np.empty((B, H, N, N), dtype=np.float64) if return_P else None
-        rc = self._lib.oracle_mha_fwd(_p(Q), _p(K), _p(V), _p(O), _p(LSE), _p(P), B * H, N, d,
+        LSE = np.empty((B, H, Nq), dtype=np.float64)
+        P = np.empty((B, H, Nq, Nk), dtype=np.float64) if return_P else None
+        rc = self._lib.oracle_mha_fwd(_p(Q), _p(K), _p(V), _p(O), _p(LSE), _p(P), B * H, Nq, Nk, d,
                                       float(scale), int(bool(causal)))
         if rc != 0:
             raise RuntimeError("oracle_mha_fwd failed (%d)" % rc)
         return (O, LSE, P) if return_P else (O, LSE)
 
     def mha_bwd(self, Q, K, V, dO, scale: float, causal: bool):
-        """dict with dQ, dK, dV [B,H,N,d], and the oracle's own O, LSE, D."""
+        """dict with dQ [B,H,Nq,d], dK, dV [B,H,Nk,d], and the oracle's own O, LSE, D."""
         Q, K, V, dO = _chk(Q, K, V, dO)
-        B, H, N, d = Q.shape
-        dQ, dK, dV, O = (np.empty_like(Q) for _ in range(4))
-        LSE = np.empty((B, H, N), dtype=np.float64)
-        D = np.empty((B, H, N), dtype=np.float64)
+        B, H, Nq, d = Q.shape
+        Nk = K.shape[2]
+        dQ, O = np.empty_like(Q), np.empty_like(Q)
+        dK, dV = np.empty_like(K), np.empty_like(K)
+        LSE = np.empty((B, H, Nq), dtype=np.float64)
+        D = np.empty((B, H, Nq), dtype=np.float64)
         rc = self._lib.oracle_mha_bwd(_p(Q), _p(K), _p(V), _p(dO), _p(dQ), _p(dK), _p(dV), _p(O),
-                                      _p(LSE), _p(D), B * H, N, d, float(scale), int(bool(causal)))
+                                      _p(LSE), _p(D), B * H, Nq, Nk, d, float(scale),
+                                      int(bool(causal)))
         if rc != 0:
             raise RuntimeError("oracle_mha_bwd failed (%d)" % rc)
         return {"dQ": dQ, "dK": dK, "dV": dV, "O": O, "LSE": LSE, "D": D}

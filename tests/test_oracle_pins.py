@@ -26,10 +26,9 @@ def rng():
 
 def numpy_attention(Q, K, V, dO, scale, causal):
     """Independent evaluation with library matmul / softmax / logsumexp."""
-    N = Q.shape[-2]
     S = scale * Q @ np.swapaxes(K, -1, -2)
     if causal:
-        S = np.where(np.tril(np.ones((N, N), dtype=bool)), S, -np.inf)
+        S = np.where(np.tril(np.ones(S.shape[-2:], dtype=bool)), S, -np.inf)
     P = softmax(S, axis=-1)
     LSE = logsumexp(S, axis=-1)
     O = P @ V
@@ -243,6 +242,105 @@ def check_large_logits_do_not_overflow(orc):
     np.testing.assert_allclose(LSE[0, 0], logsumexp(S, axis=-1), rtol=1e-13)
 
 
+RECT_SHAPES = ((5, 9), (9, 5), (1, 7), (7, 1), (40, 13))  # (Nq, Nk), non-causal only
+
+
+def check_rect_against_numpy_scipy(orc):
+    """Nq != Nk (cross-attention, Sec. 2.1): the same library evaluation, several heads."""
+    r = rng()
+    for Nq, Nk in RECT_SHAPES:
+        B, H, d, scale = 2, 3, 6, 0.45
+        Q, dO = r.standard_normal((B, H, Nq, d)) * 1.5, r.standard_normal((B, H, Nq, d))
+        K, V = r.standard_normal((B, H, Nk, d)) * 1.5, r.standard_normal((B, H, Nk, d))
+        ref = numpy_attention(Q, K, V, dO, scale, False)
+        O, LSE, P = orc.mha_fwd(Q, K, V, scale, False, return_P=True)
+        g = orc.mha_bwd(Q, K, V, dO, scale, False)
+        assert P.shape == (B, H, Nq, Nk) and g["dK"].shape == K.shape and g["dQ"].shape == Q.shape
+        np.testing.assert_allclose(P, ref["P"], rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(O, ref["O"], rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(LSE, ref["LSE"], rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(g["O"], O, rtol=0, atol=0)
+        np.testing.assert_allclose(g["D"], (dO * O).sum(-1), atol=1e-13)
+        for name in ("dQ", "dK", "dV"):
+            np.testing.assert_allclose(g[name], ref[name], rtol=1e-11, atol=1e-13, err_msg=name)
+
+
+def check_rect_single_key_closed_form(orc):
+    """Nk = 1: P = 1, so O_i = V_0, LSE_i = scale q_i.k_0, dV_0 = sum_i dO_i, dQ = dK = 0."""
+    r = rng()
+    Nq, d, scale = 11, 4, 0.8
+    Q, dO = r.standard_normal((1, 2, Nq, d)), r.standard_normal((1, 2, Nq, d))
+    K, V = r.standard_normal((1, 2, 1, d)), r.standard_normal((1, 2, 1, d))
+    g = orc.mha_bwd(Q, K, V, dO, scale, False)
+    np.testing.assert_allclose(g["O"], np.broadcast_to(V, Q.shape), atol=1e-14)
+    np.testing.assert_allclose(g["LSE"], scale * (Q * K).sum(-1), atol=1e-13)
+    np.testing.assert_allclose(g["dV"], dO.sum(2, keepdims=True), atol=1e-13)
+    assert np.abs(g["dQ"]).max() <= 1e-13 and np.abs(g["dK"]).max() <= 1e-13
+
+
+def check_rect_duplicated_keys(orc):
+    """Every key/value listed twice: O and dQ unchanged, LSE grows by ln 2, each copy gets
+    half of dK and dV.  Relates Nk keys to 2 Nk keys, so a wrong stride or bound shows."""
+    r = rng()
+    Nq, Nk, d, scale = 10, 5, 4, 0.6
+    Q, dO = r.standard_normal((1, 2, Nq, d)), r.standard_normal((1, 2, Nq, d))
+    K, V = r.standard_normal((1, 2, Nk, d)), r.standard_normal((1, 2, Nk, d))
+    g1 = orc.mha_bwd(Q, K, V, dO, scale, False)
+    g2 = orc.mha_bwd(Q, np.concatenate([K, K], 2), np.concatenate([V, V], 2), dO, scale, False)
+    np.testing.assert_allclose(g2["O"], g1["O"], atol=1e-13)
+    np.testing.assert_allclose(g2["LSE"], g1["LSE"] + math.log(2.0), atol=1e-13)
+    np.testing.assert_allclose(g2["dQ"], g1["dQ"], atol=1e-13)
+    for n in ("dK", "dV"):
+        np.testing.assert_allclose(g2[n][:, :, :Nk], 0.5 * g1[n], atol=1e-13, err_msg=n)
+        np.testing.assert_allclose(g2[n][:, :, Nk:], 0.5 * g1[n], atol=1e-13, err_msg=n)
+
+
+def check_rect_queries_are_independent(orc):
+    """Each query row is its own softmax: O, LSE, dQ of a subset of the queries equal the
+    rows of the full problem, and dK, dV add over a partition of the queries."""
+    r = rng()
+    Nq, Nk, d, scale = 12, 7, 5, 0.5
+    Q, dO = r.standard_normal((1, 2, Nq, d)), r.standard_normal((1, 2, Nq, d))
+    K, V = r.standard_normal((1, 2, Nk, d)), r.standard_normal((1, 2, Nk, d))
+    full = orc.mha_bwd(Q, K, V, dO, scale, False)
+    a = orc.mha_bwd(Q[:, :, :4], K, V, dO[:, :, :4], scale, False)
+    b = orc.mha_bwd(Q[:, :, 4:], K, V, dO[:, :, 4:], scale, False)
+    for n in ("O", "LSE", "dQ"):
+        np.testing.assert_allclose(np.concatenate([a[n], b[n]], 2), full[n], atol=1e-13, err_msg=n)
+    for n in ("dK", "dV"):
+        np.testing.assert_allclose(a[n] + b[n], full[n], atol=1e-13, err_msg=n)
+
+
+def check_rect_causal_is_rejected(orc):
+    Q, K = np.zeros((1, 1, 3, 2)), np.zeros((1, 1, 4, 2))
+    with pytest.raises(RuntimeError):
+        orc.mha_fwd(Q, K, K, 1.0, True)
+    with pytest.raises(RuntimeError):
+        orc.mha_bwd(Q, K, K, Q, 1.0, True)
+
+
+def check_rect_finite_difference_gradients(orc):
+    """dQ, dK, dV of the Nq != Nk case are the gradient of L = sum(O * dO)."""
+    r = rng()
+    scale, h = 0.6, 1e-5
+    for Nq, Nk in ((3, 6), (6, 3)):
+        Q, dO = r.standard_normal((1, 1, Nq, 3)), r.standard_normal((1, 1, Nq, 3))
+        K, V = r.standard_normal((1, 1, Nk, 3)), r.standard_normal((1, 1, Nk, 3))
+        g = orc.mha_bwd(Q, K, V, dO, scale, False)
+        base = [Q, K, V]
+        for name, idx in (("dQ", 0), ("dK", 1), ("dV", 2)):
+            num = np.zeros_like(base[idx])
+            for mi in np.ndindex(base[idx].shape):
+                ap, am = [a.copy() for a in base], [a.copy() for a in base]
+                ap[idx][mi] += h
+                am[idx][mi] -= h
+                lp = float((orc.mha_fwd(*ap, scale, False)[0] * dO).sum())
+                lm = float((orc.mha_fwd(*am, scale, False)[0] * dO).sum())
+                num[mi] = (lp - lm) / (2 * h)
+            err = np.abs(num - g[name]).max() / max(np.abs(g[name]).max(), 1e-30)
+            assert err <= 1e-6, (name, err)
+
+
 CHECKS = [
     check_rows_of_P_sum_to_one,
     check_zero_Q_gives_uniform_attention,
@@ -256,6 +354,12 @@ CHECKS = [
     check_hand_derived_rational_example,
     check_blockwise_merge_rule_equals_direct_softmax,
     check_large_logits_do_not_overflow,
+    check_rect_single_key_closed_form,
+    check_rect_duplicated_keys,
+    check_rect_queries_are_independent,
+    check_rect_finite_difference_gradients,
+    check_rect_against_numpy_scipy,
+    check_rect_causal_is_rejected,
 ]
 
 
@@ -271,15 +375,15 @@ def test_pin(check):
 # ----------------------------------------------------------------------------------------
 MISTAKES = {
     "scale dropped from the logits": ("      s *= scale;\n", ""),
-    "causal mask excludes the diagonal": ("const int jend = causal ? i + 1 : N;\n    double m = -INFINITY;",
-                                          "const int jend = causal ? (i > 0 ? i : 1) : N;\n    double m = -INFINITY;"),
+    "causal mask excludes the diagonal": ("const int jend = causal ? i + 1 : Nk;\n    double m = -INFINITY;",
+                                          "const int jend = causal ? (i > 0 ? i : 1) : Nk;\n    double m = -INFINITY;"),
     "row max not subtracted": ("Pi[j] = exp(Pi[j] - m);", "Pi[j] = exp(Pi[j]);"),
     "P not normalised": ("for (int j = 0; j < jend; ++j) Pi[j] /= l;", ""),
     "LSE is the row max": ("LSE[i] = m + log(l);", "LSE[i] = m;"),
     "O uses K instead of V": ("Oi[k] += p * V[(size_t)j * d + k];", "Oi[k] += p * V[(size_t)i * d + k];"),
     "D from dO*dO": ("Di += dOh[(size_t)i * d + k] * O[(size_t)i * d + k];", "Di += dOh[(size_t)i * d + k] * dOh[(size_t)i * d + k];"),
-    "dS sign": ("P[(size_t)i * N + j] * (dp - Di);", "P[(size_t)i * N + j] * (dp + Di);"),
-    "dS without P": ("dS[(size_t)i * N + j] = P[(size_t)i * N + j] * (dp - Di);", "dS[(size_t)i * N + j] = (dp - Di);"),
+    "dS sign": ("P[(size_t)i * Nk + j] * (dp - Di);", "P[(size_t)i * Nk + j] * (dp + Di);"),
+    "dS without P": ("dS[(size_t)i * Nk + j] = P[(size_t)i * Nk + j] * (dp - Di);", "dS[(size_t)i * Nk + j] = (dp - Di);"),
     "dP uses K instead of V": ("dp += dOh[(size_t)i * d + k] * Vh[(size_t)j * d + k];", "dp += dOh[(size_t)i * d + k] * Kh[(size_t)j * d + k];"),
     "dQ without scale": ("for (int k = 0; k < d; ++k) dQi[k] *= scale;", ""),
     "dQ contracts with Q": ("dQi[k] += ds * Kh[(size_t)j * d + k];", "dQi[k] += ds * Qh[(size_t)j * d + k];"),
@@ -287,8 +391,16 @@ MISTAKES = {
     "dK from P instead of dS": ("dKj[k] += ds * Qh[(size_t)i * d + k];", "dKj[k] += p * Qh[(size_t)i * d + k];"),
     "dK with the wrong Q row": ("dKj[k] += ds * Qh[(size_t)i * d + k];", "dKj[k] += ds * Qh[(size_t)j * d + k];"),
     "dV from dS instead of P": ("dVj[k] += p * dOh[(size_t)i * d + k];", "dVj[k] += ds * dOh[(size_t)i * d + k];"),
-    "dV transposed P": ("const double p = P[(size_t)i * N + j];\n        const double ds", "const double p = P[(size_t)j * N + i];\n        const double ds"),
+    "dV transposed P": ("const double p = P[(size_t)i * Nk + j];\n        const double ds", "const double p = P[(size_t)j * Nk + i];\n        const double ds"),
     "causal backward starts one row late": ("const int ibeg = causal ? j : 0;", "const int ibeg = causal ? j + 1 : 0;"),
+    # mistakes that only a problem with Nq != Nk can show
+    "dK/dV sum over Nk queries": ("for (int i = ibeg; i < Nq; ++i) {", "for (int i = ibeg; i < (Nq < Nk ? Nq : Nk); ++i) {"),
+    "softmax over the first Nq keys": ("const int jend = causal ? i + 1 : Nk;\n    double m = -INFINITY;",
+                                       "const int jend = causal ? i + 1 : (Nq < Nk ? Nq : Nk);\n    double m = -INFINITY;"),
+    "dQ sums over the first Nq keys": ("const int jend = causal ? i + 1 : Nk;\n      for (int j = 0; j < jend; ++j) {\n        double dp",
+                                       "const int jend = causal ? i + 1 : (Nq < Nk ? Nq : Nk);\n      for (int j = 0; j < jend; ++j) {\n        double dp"),
+    "K and V of head h taken at the Q offset": ("*Kh = K + offk, *Vh = V + offk,", "*Kh = K + (Nq < Nk ? offq : offk), *Vh = V + (Nq < Nk ? offq : offk),"),
+    "LSE_out rows strided by Nk": ("LSE_out[(size_t)h * Nq + i] = LSE[i];", "LSE_out[(size_t)h * (Nq < Nk ? Nq : Nk) + i] = LSE[i];"),
 }
 
 
