@@ -1,7 +1,8 @@
 /*
  * spark_mha.h -- C ABI of the fused multi-head-attention library for MI355X (gfx950).
  *
- * Two operations, each enqueued on a caller-provided HIP stream:
+ * Two operations, each enqueued on a caller-provided HIP stream, each in a self-attention
+ * form (one sequence length N) and a cross-attention form (Nq queries, Nk keys/values):
  *
  *   spark_mha_fwd : O = softmax(scale * Q K^T [+ causal mask]) V, and the row
  *                   statistic LSE that the backward needs.
@@ -24,6 +25,12 @@
  *     a flag (0 = all keys, nonzero = masked).  Size limits: B*H*ceil(N/64) < 2^31 and
  *     N*d < 2^31.  Anything else returns SPARK_ERR_SHAPE; nothing is silently mis-computed.
  *   - causal != 0: query i attends to keys j <= i (Sec. 2.1, masked MHA).
+ *   - The spark_mha_cross_* entry points take Nq query rows and Nk key/value rows (Sec. 2.1:
+ *     the decoder's second attention layer attends to the encoder output, so S of Eq. 1 is
+ *     Nq x Nk there).  Q, O, dO, dQ are then [B, H, Nq, d]; K, V, dK, dV are [B, H, Nk, d];
+ *     LSE is [B, H, Nq].  Nq, Nk >= 1, each under the limits stated for N.  The causal
+ *     mask is defined for Nq == Nk only: causal != 0 with Nq != Nk returns SPARK_ERR_SHAPE.
+ *     spark_mha_fwd / spark_mha_bwd are exactly the cross forms with Nq = Nk = N.
  *   - Arithmetic: both contractions run on fp16/bf16 MFMA with fp32
  *     accumulation; the softmax statistics, P before packing, the O
  *     accumulator, LSE, D and dS before packing are fp32 (Sec. 3.2.1: softmax in
@@ -50,7 +57,7 @@ typedef enum {
   SPARK_OK = 0,
   SPARK_ERR_NULL = -1,      /* a required pointer is NULL */
   SPARK_ERR_SHAPE = -2,     /* B, H or N < 1; d not 64/128; a size limit exceeded; scale not
-                               finite or <= 0 */
+                               finite or <= 0; causal with Nq != Nk */
   SPARK_ERR_DTYPE = -3,     /* dtype is neither SPARK_F16 nor SPARK_BF16 */
   SPARK_ERR_ALIGN = -4,     /* a pointer is not 16-byte aligned */
   SPARK_ERR_WORKSPACE = -5, /* workspace too small (see spark_mha_bwd_workspace_bytes) */
@@ -106,6 +113,36 @@ int spark_mha_bwd_marked(const void* Q, const void* K, const void* V, const void
                          void* workspace, size_t workspace_bytes,
                          int B, int H, int N, int d, float scale, int causal,
                          spark_dtype_t dtype, void* stream, void* const events[4]);
+
+/*
+ * Cross-attention forward: Eq. 1 with S = scale * Q K^T of shape Nq x Nk (Sec. 2.1, second
+ * attention layer of the decoder); same kernel, arithmetic and guarantees as spark_mha_fwd.
+ *   Q       : in,  device, [B,H,Nq,d] dtype
+ *   K, V    : in,  device, [B,H,Nk,d] dtype
+ *   O       : out, device, [B,H,Nq,d] dtype, fully overwritten
+ *   LSE     : out, device, [B,H,Nq] fp32
+ */
+int spark_mha_cross_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                        int B, int H, int Nq, int Nk, int d, float scale, int causal,
+                        spark_dtype_t dtype, void* stream);
+
+/* Workspace bytes of spark_mha_cross_bwd: two fp32 [B,H,Nq] arrays.  0 for invalid shapes. */
+size_t spark_mha_cross_bwd_workspace_bytes(int B, int H, int Nq, int Nk, int d,
+                                           spark_dtype_t dtype);
+
+/*
+ * Cross-attention backward (Sec. 3.3, Eq. 4 with an Nq x Nk score matrix).
+ *   Q, O, dO   : in,  device, [B,H,Nq,d] dtype;   K, V : in, device, [B,H,Nk,d] dtype
+ *   LSE        : in,  device, [B,H,Nq] fp32 (as written by spark_mha_cross_fwd)
+ *   dQ         : out, device, [B,H,Nq,d] dtype;   dK, dV : out, device, [B,H,Nk,d] dtype
+ *   workspace  : at least spark_mha_cross_bwd_workspace_bytes(...) bytes, 16-byte aligned
+ * Same kernels, order and guarantees as spark_mha_bwd.
+ */
+int spark_mha_cross_bwd(const void* Q, const void* K, const void* V, const void* O,
+                        const float* LSE, const void* dO, void* dQ, void* dK, void* dV,
+                        void* workspace, size_t workspace_bytes,
+                        int B, int H, int Nq, int Nk, int d, float scale, int causal,
+                        spark_dtype_t dtype, void* stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char* spark_status_str(int status);

@@ -10,6 +10,9 @@ from .binding import (  # noqa: F401
     load_library,
     spark_mha_bwd,
     spark_mha_bwd_workspace_bytes,
+    spark_mha_cross_bwd,
+    spark_mha_cross_bwd_workspace_bytes,
+    spark_mha_cross_fwd,
     spark_mha_fwd,
     status_str,
 )

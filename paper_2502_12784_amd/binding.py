@@ -17,7 +17,8 @@ SPARK_F16 = 0
 SPARK_BF16 = 1
 
 EXPORTS = ("spark_mha_fwd", "spark_mha_bwd", "spark_mha_bwd_marked",
-           "spark_mha_bwd_workspace_bytes", "spark_status_str")
+           "spark_mha_bwd_workspace_bytes", "spark_mha_cross_fwd", "spark_mha_cross_bwd",
+           "spark_mha_cross_bwd_workspace_bytes", "spark_status_str")
 
 _lib = None
 
@@ -44,6 +45,12 @@ def load_library() -> ctypes.CDLL:
     lib.spark_mha_bwd_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.spark_mha_bwd.restype = i
     lib.spark_mha_bwd.argtypes = [vp] * 10 + [ctypes.c_size_t, i, i, i, i, f, i, i, vp]
+    lib.spark_mha_cross_fwd.restype = i
+    lib.spark_mha_cross_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, f, i, i, vp]
+    lib.spark_mha_cross_bwd_workspace_bytes.restype = ctypes.c_size_t
+    lib.spark_mha_cross_bwd_workspace_bytes.argtypes = [i, i, i, i, i, i]
+    lib.spark_mha_cross_bwd.restype = i
+    lib.spark_mha_cross_bwd.argtypes = [vp] * 10 + [ctypes.c_size_t, i, i, i, i, i, f, i, i, vp]
     lib.spark_mha_bwd_marked.restype = i
     lib.spark_mha_bwd_marked.argtypes = lib.spark_mha_bwd.argtypes + [ctypes.POINTER(vp)]
     lib.spark_status_str.restype = ctypes.c_char_p
@@ -102,6 +109,62 @@ def spark_mha_fwd(Q, K, V, scale: float, causal: bool, O=None, LSE=None):
 
 def spark_mha_bwd_workspace_bytes(B: int, H: int, N: int, d: int, dtype_code: int) -> int:
     return int(load_library().spark_mha_bwd_workspace_bytes(B, H, N, d, dtype_code))
+
+
+def spark_mha_cross_bwd_workspace_bytes(B: int, H: int, Nq: int, Nk: int, d: int,
+                                        dtype_code: int) -> int:
+    return int(load_library().spark_mha_cross_bwd_workspace_bytes(B, H, Nq, Nk, d, dtype_code))
+
+
+def spark_mha_cross_fwd(Q, K, V, scale: float, causal: bool = False, O=None, LSE=None):
+    """O, LSE for Q [B,H,Nq,d] attending to K, V [B,H,Nk,d] (Nq and Nk may differ)."""
+    import torch
+    lib = load_library()
+    B, H, Nq, d = Q.shape
+    Nk = K.shape[2]
+    _require(Q, (B, H, Nq, d), Q.dtype, "Q")
+    for t, n in ((K, "K"), (V, "V")):
+        _require(t, (B, H, Nk, d), Q.dtype, n)
+    if O is None:
+        O = torch.empty_like(Q)
+    if LSE is None:
+        LSE = torch.empty((B, H, Nq), dtype=torch.float32, device=Q.device)
+    _require(O, (B, H, Nq, d), Q.dtype, "O")
+    _require(LSE, (B, H, Nq), torch.float32, "LSE")
+    _check(lib.spark_mha_cross_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                                   LSE.data_ptr(), B, H, Nq, Nk, d, float(scale),
+                                   int(bool(causal)), _dtype_code(Q), _stream_ptr()))
+    return O, LSE
+
+
+def spark_mha_cross_bwd(Q, K, V, O, LSE, dO, scale: float, causal: bool = False, dQ=None,
+                        dK=None, dV=None, workspace=None):
+    """dQ [B,H,Nq,d], dK, dV [B,H,Nk,d] for the problem of spark_mha_cross_fwd."""
+    import torch
+    lib = load_library()
+    B, H, Nq, d = Q.shape
+    Nk = K.shape[2]
+    for t, n in ((Q, "Q"), (O, "O"), (dO, "dO")):
+        _require(t, (B, H, Nq, d), Q.dtype, n)
+    for t, n in ((K, "K"), (V, "V")):
+        _require(t, (B, H, Nk, d), Q.dtype, n)
+    _require(LSE, (B, H, Nq), torch.float32, "LSE")
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(K) if dV is None else dV
+    _require(dQ, (B, H, Nq, d), Q.dtype, "dQ")
+    for t, n in ((dK, "dK"), (dV, "dV")):
+        _require(t, (B, H, Nk, d), Q.dtype, n)
+    code = _dtype_code(Q)
+    need = spark_mha_cross_bwd_workspace_bytes(B, H, Nq, Nk, d, code)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
+    wbytes = workspace.numel() * workspace.element_size()
+    _check(lib.spark_mha_cross_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                                   LSE.data_ptr(), dO.data_ptr(), dQ.data_ptr(), dK.data_ptr(),
+                                   dV.data_ptr(), workspace.data_ptr(), wbytes, B, H, Nq, Nk, d,
+                                   float(scale), int(bool(causal)), code, _stream_ptr()))
+    return dQ, dK, dV
 
 
 class HipEvents:

@@ -83,7 +83,7 @@ template <typename T, int D, bool CAUSAL>
 __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Dws,
-    T* __restrict__ dK, T* __restrict__ dV, int N, int nkt, float scale, float scale_log2) {
+    T* __restrict__ dK, T* __restrict__ dV, int Nq, int Nk, int nkt, float scale, float scale_log2) {
   using F = Frag<T>;
   using v8 = typename F::v8;
   using C = BwdKvCfg<D>;
@@ -101,10 +101,11 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_kernel(
   const int head = logical / items;
   const int item = logical - head * items;
 
-  const size_t head_off = (size_t)head * N * D;
-  const float* LSEh = LSE + (size_t)head * N;
-  const float* Dh = Dws + (size_t)head * N;
-  const BufView qview(Q + head_off, (uint32_t)N * D * 2), doview(dO + head_off, (uint32_t)N * D * 2);
+  const size_t head_off = (size_t)head * Nq * D;    // Q, dO
+  const size_t head_off_k = (size_t)head * Nk * D;  // K, V, dK, dV
+  const float* LSEh = LSE + (size_t)head * Nq;
+  const float* Dh = Dws + (size_t)head * Nq;
+  const BufView qview(Q + head_off, (uint32_t)Nq * D * 2), doview(dO + head_off, (uint32_t)Nq * D * 2);
 
   for (int rep = 0; rep < (CAUSAL ? 2 : 1); ++rep) {
     const int kt = CAUSAL ? (rep == 0 ? item : nkt - 1 - item) : item;  // the long tile first
@@ -114,13 +115,13 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_kernel(
     }
     const int k0w = kt * C::BN + wave * 32;  // first key of this wave
     const int krow = k0w + c32;
-    const int krow_c = krow < N ? krow : N - 1;
+    const int krow_c = krow < Nk ? krow : Nk - 1;
 
     v8 kf[KS], vf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      kf[ks] = *reinterpret_cast<const v8*>(K + head_off + (size_t)krow_c * D + ks * 16 + g * 8);
-      vf[ks] = *reinterpret_cast<const v8*>(V + head_off + (size_t)krow_c * D + ks * 16 + g * 8);
+      kf[ks] = *reinterpret_cast<const v8*>(K + head_off_k + (size_t)krow_c * D + ks * 16 + g * 8);
+      vf[ks] = *reinterpret_cast<const v8*>(V + head_off_k + (size_t)krow_c * D + ks * 16 + g * 8);
     }
 
     f32x16 dk[DT], dv[DT];
@@ -129,7 +130,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) { dk[dt][r] = 0.f; dv[dt][r] = 0.f; }
 
-    const int ns = (N + C::BM - 1) / C::BM;                 // query stages in the sequence
+    const int ns = (Nq + C::BM - 1) / C::BM;                // query stages in the sequence
     const int s_begin = CAUSAL ? (kt * C::BN) / C::BM : 0;  // earlier queries see none of this tile
 
     // Per-lane LDS read offsets of the current buffer; switching buffers is one XOR each.
@@ -149,9 +150,9 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_kernel(
         // contractions directly.  Rows past the end get -inf (P = 0 there) and D = 0.
         // raw values only: any arithmetic on them here would force a wait for the loads
         if (tid < C::BM)
-          statreg = row < N ? LSEh[row] : INFINITY;
+          statreg = row < Nq ? LSEh[row] : INFINITY;
         else
-          statreg = row < N ? Dh[row] : 0.f;
+          statreg = row < Nq ? Dh[row] : 0.f;
       }
     };
     auto store_stage = [&](int buf) {
@@ -180,7 +181,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_kernel(
       for (int sub = 0; sub < C::BM / 32; ++sub) {
         const int q0s = m * C::BM + sub * 32;
         if (CAUSAL && q0s + 31 < k0w) continue;  // every query here precedes every key of the wave
-        if (q0s >= N) continue;
+        if (q0s >= Nq) continue;
         constexpr int NG = KS / 2;
         const int suboff = sub * 32 * C::ROWB;
 
@@ -280,8 +281,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_kernel(
     }
 
     SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
-    store_transposed<T, D, C::OSTR>(dk, scale, ob, dK + head_off, k0w, N, lane);
-    store_transposed<T, D, C::OSTR>(dv, 1.0f, ob, dV + head_off, k0w, N, lane);
+    store_transposed<T, D, C::OSTR>(dk, scale, ob, dK + head_off_k, k0w, Nk, lane);
+    store_transposed<T, D, C::OSTR>(dv, 1.0f, ob, dV + head_off_k, k0w, Nk, lane);
   }  // rep
 }
 
@@ -318,7 +319,7 @@ template <typename T, int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ dO, const float* __restrict__ LSE2, const float* __restrict__ Dws,
-    T* __restrict__ dK, T* __restrict__ dV, int N, int nkt, float scale) {
+    T* __restrict__ dK, T* __restrict__ dV, int Nq, int Nk, int nkt, float scale) {
   using F = Frag<T>;
   using v8 = typename F::v8;
   using C = BwdKvPipeCfg<D>;
@@ -335,9 +336,10 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
   const int head = logical / items;
   const int item = logical - head * items;
 
-  const size_t head_off = (size_t)head * N * D;
-  const BufView qview(Q + head_off, (uint32_t)N * D * 2), doview(dO + head_off, (uint32_t)N * D * 2);
-  const BufView lview(LSE2 + (size_t)head * N, (uint32_t)N * 4), dview(Dws + (size_t)head * N, (uint32_t)N * 4);
+  const size_t head_off = (size_t)head * Nq * D;    // Q, dO
+  const size_t head_off_k = (size_t)head * Nk * D;  // K, V, dK, dV
+  const BufView qview(Q + head_off, (uint32_t)Nq * D * 2), doview(dO + head_off, (uint32_t)Nq * D * 2);
+  const BufView lview(LSE2 + (size_t)head * Nq, (uint32_t)Nq * 4), dview(Dws + (size_t)head * Nq, (uint32_t)Nq * 4);
   const uint32_t lane_src = dma_lane_src<D>(wave, lane);
   const float scale_log2 = scale * 1.4426950408889634f;
 
@@ -349,13 +351,13 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
     }
     const int k0w = kt * C::BN + wave * 32;
     const int krow = k0w + c32;
-    const int krow_c = krow < N ? krow : N - 1;
+    const int krow_c = krow < Nk ? krow : Nk - 1;
 
     v8 kf[KS], vf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      kf[ks] = *reinterpret_cast<const v8*>(K + head_off + (size_t)krow_c * D + ks * 16 + g * 8);
-      vf[ks] = *reinterpret_cast<const v8*>(V + head_off + (size_t)krow_c * D + ks * 16 + g * 8);
+      kf[ks] = *reinterpret_cast<const v8*>(K + head_off_k + (size_t)krow_c * D + ks * 16 + g * 8);
+      vf[ks] = *reinterpret_cast<const v8*>(V + head_off_k + (size_t)krow_c * D + ks * 16 + g * 8);
     }
 
     f32x16 dk[DT], dv[DT];
@@ -364,7 +366,7 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) { dk[dt][r] = 0.f; dv[dt][r] = 0.f; }
 
-    const int ns = (N + C::BM - 1) / C::BM;
+    const int ns = (Nq + C::BM - 1) / C::BM;
     const int s_begin = CAUSAL ? (kt * C::BN) / C::BM : 0;
 
     const SwzLane<D> lane_off(lane);  // offsets inside slot 0
@@ -577,8 +579,8 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
     }
 
     SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
-    store_transposed<T, D, C::OSTR>(dk, scale, ob, dK + head_off, k0w, N, lane);
-    store_transposed<T, D, C::OSTR>(dv, 1.0f, ob, dV + head_off, k0w, N, lane);
+    store_transposed<T, D, C::OSTR>(dk, scale, ob, dK + head_off_k, k0w, Nk, lane);
+    store_transposed<T, D, C::OSTR>(dv, 1.0f, ob, dV + head_off_k, k0w, Nk, lane);
   }  // rep
 }
 
@@ -602,7 +604,7 @@ template <typename T, int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Dws,
-    T* __restrict__ dQ, int N, int nqt, float scale, float scale_log2) {
+    T* __restrict__ dQ, int Nq, int Nk, int nqt, float scale, float scale_log2) {
   using F = Frag<T>;
   using v8 = typename F::v8;
   using C = BwdQCfg<D>;
@@ -620,8 +622,9 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
   const int head = logical / items;
   const int item = logical - head * items;
 
-  const size_t head_off = (size_t)head * N * D;
-  const BufView kview(K + head_off, (uint32_t)N * D * 2), vview(V + head_off, (uint32_t)N * D * 2);
+  const size_t head_off = (size_t)head * Nq * D;    // Q, dO, dQ
+  const size_t head_off_k = (size_t)head * Nk * D;  // K, V
+  const BufView kview(K + head_off_k, (uint32_t)Nk * D * 2), vview(V + head_off_k, (uint32_t)Nk * D * 2);
 
   for (int rep = 0; rep < (CAUSAL ? 2 : 1); ++rep) {
     const int qt = CAUSAL ? (rep == 0 ? nqt - 1 - item : item) : item;  // the long tile first
@@ -631,7 +634,7 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
     }
     const int q0 = qt * C::BM + wave * 32;
     const int qrow = q0 + c32;
-    const int qrow_c = qrow < N ? qrow : N - 1;
+    const int qrow_c = qrow < Nq ? qrow : Nq - 1;
 
     v8 qf[KS], dof[KS];
 #pragma unroll
@@ -639,13 +642,13 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
       qf[ks] = *reinterpret_cast<const v8*>(Q + head_off + (size_t)qrow_c * D + ks * 16 + g * 8);
       dof[ks] = *reinterpret_cast<const v8*>(dO + head_off + (size_t)qrow_c * D + ks * 16 + g * 8);
     }
-    float lse2 = LSE[(size_t)head * N + qrow_c] * 1.4426950408889634f;
-    float Dq = Dws[(size_t)head * N + qrow_c];
+    float lse2 = LSE[(size_t)head * Nq + qrow_c] * 1.4426950408889634f;
+    float Dq = Dws[(size_t)head * Nq + qrow_c];
 
-    int kv_end = N;
+    int kv_end = Nk;
     if (CAUSAL) {
       const int lim = (qt + 1) * C::BM;
-      kv_end = lim < N ? lim : N;
+      kv_end = lim < Nk ? lim : Nk;
     }
     const int nt = (kv_end + C::BN - 1) / C::BN;
 
@@ -724,7 +727,7 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
         sched_fence();
 
         float ds[16 * MT];
-        const bool need_mask = (CAUSAL && k0 + C::BN - 1 > q0) || (k0 + C::BN > N);
+        const bool need_mask = (CAUSAL && k0 + C::BN - 1 > q0) || (k0 + C::BN > Nk);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -732,7 +735,7 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
             float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mt][r], scale_log2, -lse2));
             if (need_mask) {
               const int key = k0 + mt * 32 + 8 * (r / 4) + 4 * g + (r % 4);
-              const bool ok = key < N && (!CAUSAL || key <= qrow);
+              const bool ok = key < Nk && (!CAUSAL || key <= qrow);
               if (!ok) pe = 0.f;
             }
             ds[mt * 16 + r] = pe * (dp[mt][r] - Dq);
@@ -765,7 +768,7 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
     }
 
     SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
-    store_transposed<T, D, C::OSTR>(dq, scale, ob, dQ + head_off, q0, N, lane);
+    store_transposed<T, D, C::OSTR>(dq, scale, ob, dQ + head_off, q0, Nq, lane);
   }  // rep
 }
 

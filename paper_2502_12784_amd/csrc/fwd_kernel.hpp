@@ -49,7 +49,7 @@ template <int D> struct FwdCfg {
 template <typename T, int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
-    T* __restrict__ O, float* __restrict__ LSE, int N, int nqt, float scale_log2) {
+    T* __restrict__ O, float* __restrict__ LSE, int Nq, int Nk, int nqt, float scale_log2) {
   using F = Frag<T>;
   using v8 = typename F::v8;
   using v4 = typename F::v4;
@@ -73,10 +73,12 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
   const int head = logical / items;
   const int item = logical - head * items;
 
-  const size_t head_off = (size_t)head * N * D;
+  // Nq query rows and Nk key rows per head (equal for self-attention; causal needs them equal)
+  const size_t head_off = (size_t)head * Nq * D;
+  const size_t head_off_k = (size_t)head * Nk * D;
   const T* Qh = Q + head_off;
-  const T* Kh = K + head_off;
-  const T* Vh = V + head_off;
+  const T* Kh = K + head_off_k;
+  const T* Vh = V + head_off_k;
 
   for (int rep = 0; rep < (CAUSAL ? 2 : 1); ++rep) {
     const int qt = CAUSAL ? (rep == 0 ? nqt - 1 - item : item) : item;
@@ -87,22 +89,22 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
 
     const int q0 = qt * C::BM + wave * 32;  // first query row of this wave
     const int qrow = q0 + c32;              // this lane's query row
-    const int qrow_c = qrow < N ? qrow : N - 1;
+    const int qrow_c = qrow < Nq ? qrow : Nq - 1;
 
     v8 qf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
       qf[ks] = *reinterpret_cast<const v8*>(Qh + (size_t)qrow_c * D + ks * 16 + g * 8);
 
-    int kv_end = N;
+    int kv_end = Nk;
     if (CAUSAL) {
       const int lim = (qt + 1) * C::BM;
-      kv_end = lim < N ? lim : N;
+      kv_end = lim < Nk ? lim : Nk;
     }
     const int nt = (kv_end + C::BN - 1) / C::BN;
 
     // Tile loads: thread t owns 16-byte chunk t of each group of 256 chunks (= 4096 bytes).
-    const BufView kview(Kh, (uint32_t)N * D * 2), vview(Vh, (uint32_t)N * D * 2);
+    const BufView kview(Kh, (uint32_t)Nk * D * 2), vview(Vh, (uint32_t)Nk * D * 2);
     u32x4 kreg[NLD], vreg[NLD];
     auto load_tile = [&](int j) {
       const uint32_t tile_off = (uint32_t)j * (C::BN * D * 2);
@@ -182,7 +184,7 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
           }
         };
 
-        const bool need_mask = (CAUSAL && k0 + C::BN - 1 > q0) || (k0 + C::BN > N);
+        const bool need_mask = (CAUSAL && k0 + C::BN - 1 > q0) || (k0 + C::BN > Nk);
         float t[32];
         // raw scores of one half -> t, masked; returns the scaled row maximum of the half
         auto half_max = [&](int h) {
@@ -192,7 +194,7 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
               const int key = k0 + h * 32 + 8 * (r / 4) + 4 * g + (r % 4);
-              const bool ok = key < N && (!CAUSAL || key <= qrow);
+              const bool ok = key < Nk && (!CAUSAL || key <= qrow);
               if (!ok) t[h * 16 + r] = -INFINITY;
             }
           }
@@ -325,10 +327,10 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
     for (int p = 0; p < 32 / RPP; ++p) {
       const int row = p * RPP + lane / CPR, cc = lane % CPR;
       const u32x4 v = lds_read16<u32x4>(ob, row * C::OSTR + cc * 16);
-      if (q0 + row < N) *reinterpret_cast<u32x4*>(Oh + (size_t)(q0 + row) * D + cc * 8) = v;
+      if (q0 + row < Nq) *reinterpret_cast<u32x4*>(Oh + (size_t)(q0 + row) * D + cc * 8) = v;
     }
-    if (g == 0 && qrow < N)
-      LSE[(size_t)head * N + qrow] = (m_run + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f;
+    if (g == 0 && qrow < Nq)
+      LSE[(size_t)head * Nq + qrow] = (m_run + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f;
   }  // rep
 }
 

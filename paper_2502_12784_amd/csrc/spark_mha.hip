@@ -15,15 +15,18 @@ using namespace spark;
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int check_common(int B, int H, int N, int d, float scale, int dtype) {
+// Nq queries attend to Nk keys; self-attention passes the same N twice.
+int check_common(int B, int H, int Nq, int Nk, int d, float scale, int causal, int dtype) {
   if (dtype != SPARK_F16 && dtype != SPARK_BF16) return SPARK_ERR_DTYPE;
-  if (B < 1 || H < 1 || N < 1) return SPARK_ERR_SHAPE;
+  if (B < 1 || H < 1 || Nq < 1 || Nk < 1) return SPARK_ERR_SHAPE;
+  if (causal && Nq != Nk) return SPARK_ERR_SHAPE;  // the mask is defined for a square S only
   if (d != 64 && d != 128) return SPARK_ERR_SHAPE;
   if (!isfinite(scale) || !(scale > 0.f)) return SPARK_ERR_SHAPE;
   const int64_t bh = (int64_t)B * H;
-  const int64_t tiles64 = ((int64_t)N + 63) / 64;
+  const int64_t nmax = Nq > Nk ? Nq : Nk;
+  const int64_t tiles64 = (nmax + 63) / 64;
   if (bh * tiles64 >= (int64_t)1 << 31) return SPARK_ERR_SHAPE;
-  if ((int64_t)N * d >= (int64_t)1 << 31) return SPARK_ERR_SHAPE;
+  if (nmax * d >= (int64_t)1 << 31) return SPARK_ERR_SHAPE;
   return SPARK_OK;
 }
 
@@ -35,23 +38,23 @@ int set_smem(KernelT kernel, int bytes) {
 }
 
 template <typename T, int D, bool CAUSAL>
-int launch_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int BH, int N,
-               float scale, hipStream_t st) {
+int launch_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int BH, int Nq,
+               int Nk, float scale, hipStream_t st) {
   using C = FwdCfg<D>;
   auto kernel = mha_fwd_kernel<T, D, CAUSAL>;
   static const int attr = set_smem(kernel, C::SMEM);
   if (attr != SPARK_OK) return attr;
-  const int nqt = (N + C::BM - 1) / C::BM;
+  const int nqt = (Nq + C::BM - 1) / C::BM;
   const float scale_log2 = scale * 1.4426950408889634f;
   hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nqt))), dim3(256), C::SMEM, st,
                      static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
-                     static_cast<T*>(O), LSE, N, nqt, scale_log2);
+                     static_cast<T*>(O), LSE, Nq, Nk, nqt, scale_log2);
   return hipGetLastError() == hipSuccess ? SPARK_OK : SPARK_ERR_LAUNCH;
 }
 
 template <typename T, int D, bool CAUSAL>
 int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
-               const void* dO, void* dQ, void* dK, void* dV, float* Dws, int BH, int N,
+               const void* dO, void* dQ, void* dK, void* dV, float* Dws, int BH, int Nq, int Nk,
                float scale, hipStream_t st, void* const* ev) {
   const T* q = static_cast<const T*>(Q);
   const T* k = static_cast<const T*>(K);
@@ -59,7 +62,7 @@ int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const
   const T* o = static_cast<const T*>(O);
   const T* dout = static_cast<const T*>(dO);
   const float scale_log2 = scale * 1.4426950408889634f;
-  float* LSE2ws = Dws + (size_t)BH * N;  // second half of the workspace: LSE * log2(e)
+  float* LSE2ws = Dws + (size_t)BH * Nq;  // second half of the workspace: LSE * log2(e)
   // optional profiling marks between the kernels (spark_mha_bwd_marked)
   auto mark = [&](int i) {
     return !ev || hipEventRecord(static_cast<hipEvent_t>(ev[i]), st) == hipSuccess;
@@ -68,7 +71,7 @@ int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const
   if (!mark(0)) return SPARK_ERR_LAUNCH;
   {  // D = rowsum(dO o O): one wave per 64/(D/8) rows
     constexpr int ROWS_PER_BLOCK = 256 / (D / 8);
-    const int64_t rows = (int64_t)BH * N;
+    const int64_t rows = (int64_t)BH * Nq;
     const unsigned grid = (unsigned)((rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK);
     hipLaunchKernelGGL((mha_bwd_dot_kernel<T, D>), dim3(grid), dim3(256), 0, st, o, dout, LSE, Dws,
                        LSE2ws, rows);
@@ -79,18 +82,18 @@ int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const
     auto kernel = mha_bwd_dkdv_pipe_kernel<T, D, CAUSAL>;
     static const int attr = set_smem(kernel, C::SMEM);
     if (attr != SPARK_OK) return attr;
-    const int nkt = (N + C::BN - 1) / C::BN;
+    const int nkt = (Nk + C::BN - 1) / C::BN;
     hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nkt))), dim3(256), C::SMEM, st, q, k, v, dout,
-                       LSE2ws, Dws, static_cast<T*>(dK), static_cast<T*>(dV), N, nkt, scale);
+                       LSE2ws, Dws, static_cast<T*>(dK), static_cast<T*>(dV), Nq, Nk, nkt, scale);
     if (hipGetLastError() != hipSuccess || !mark(2)) return SPARK_ERR_LAUNCH;
   } else {  // dK, dV: one workgroup per tile of 128 keys, two workgroups per CU
     using C = BwdKvCfg<D>;
     auto kernel = mha_bwd_dkdv_kernel<T, D, CAUSAL>;
     static const int attr = set_smem(kernel, C::SMEM);
     if (attr != SPARK_OK) return attr;
-    const int nkt = (N + C::BN - 1) / C::BN;
+    const int nkt = (Nk + C::BN - 1) / C::BN;
     hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nkt))), dim3(256), C::SMEM, st, q, k, v, dout,
-                       LSE, Dws, static_cast<T*>(dK), static_cast<T*>(dV), N, nkt, scale,
+                       LSE, Dws, static_cast<T*>(dK), static_cast<T*>(dV), Nq, Nk, nkt, scale,
                        scale_log2);
     if (hipGetLastError() != hipSuccess || !mark(2)) return SPARK_ERR_LAUNCH;
   }
@@ -99,9 +102,9 @@ int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const
     auto kernel = mha_bwd_dq_kernel<T, D, CAUSAL>;
     static const int attr = set_smem(kernel, C::SMEM);
     if (attr != SPARK_OK) return attr;
-    const int nqt = (N + C::BM - 1) / C::BM;
+    const int nqt = (Nq + C::BM - 1) / C::BM;
     hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nqt))), dim3(256), C::SMEM, st, q, k, v, dout,
-                       LSE, Dws, static_cast<T*>(dQ), N, nqt, scale, scale_log2);
+                       LSE, Dws, static_cast<T*>(dQ), Nq, Nk, nqt, scale, scale_log2);
     if (hipGetLastError() != hipSuccess || !mark(3)) return SPARK_ERR_LAUNCH;
   }
   return SPARK_OK;
@@ -126,49 +129,68 @@ int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const
 
 extern "C" {
 
-int spark_mha_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H,
-                  int N, int d, float scale, int causal, spark_dtype_t dtype_e, void* stream) {
+int spark_mha_cross_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
+                        int H, int Nq, int Nk, int d, float scale, int causal,
+                        spark_dtype_t dtype_e, void* stream) {
   const int dtype = (int)dtype_e;
   if (!Q || !K || !V || !O || !LSE) return SPARK_ERR_NULL;
-  const int rc = check_common(B, H, N, d, scale, dtype);
+  const int rc = check_common(B, H, Nq, Nk, d, scale, causal, dtype);
   if (rc != SPARK_OK) return rc;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE))
     return SPARK_ERR_ALIGN;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int BH = B * H;
-  SPARK_DISPATCH(launch_fwd, Q, K, V, O, LSE, BH, N, scale, st);
+  SPARK_DISPATCH(launch_fwd, Q, K, V, O, LSE, BH, Nq, Nk, scale, st);
+}
+
+int spark_mha_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H,
+                  int N, int d, float scale, int causal, spark_dtype_t dtype, void* stream) {
+  return spark_mha_cross_fwd(Q, K, V, O, LSE, B, H, N, N, d, scale, causal, dtype, stream);
+}
+
+size_t spark_mha_cross_bwd_workspace_bytes(int B, int H, int Nq, int Nk, int d,
+                                           spark_dtype_t dtype) {
+  if (check_common(B, H, Nq, Nk, d, 1.0f, 0, (int)dtype) != SPARK_OK) return 0;
+  return 2 * (size_t)B * H * Nq * sizeof(float);  // D and LSE*log2(e), fp32 [B,H,Nq] each
 }
 
 size_t spark_mha_bwd_workspace_bytes(int B, int H, int N, int d, spark_dtype_t dtype) {
-  if (check_common(B, H, N, d, 1.0f, (int)dtype) != SPARK_OK) return 0;
-  return 2 * (size_t)B * H * N * sizeof(float);  // D and LSE*log2(e), fp32 [B,H,N] each
+  return spark_mha_cross_bwd_workspace_bytes(B, H, N, N, d, dtype);
 }
 
 static int bwd_impl(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
                     const void* dO, void* dQ, void* dK, void* dV, void* workspace,
-                    size_t workspace_bytes, int B, int H, int N, int d, float scale, int causal,
-                    spark_dtype_t dtype_e, void* stream, void* const* ev) {
+                    size_t workspace_bytes, int B, int H, int Nq, int Nk, int d, float scale,
+                    int causal, spark_dtype_t dtype_e, void* stream, void* const* ev) {
   const int dtype = (int)dtype_e;
   if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV || !workspace) return SPARK_ERR_NULL;
-  const int rc = check_common(B, H, N, d, scale, dtype);
+  const int rc = check_common(B, H, Nq, Nk, d, scale, causal, dtype);
   if (rc != SPARK_OK) return rc;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE) ||
       !aligned16(dO) || !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
     return SPARK_ERR_ALIGN;
-  if (workspace_bytes < spark_mha_bwd_workspace_bytes(B, H, N, d, dtype_e))
+  if (workspace_bytes < spark_mha_cross_bwd_workspace_bytes(B, H, Nq, Nk, d, dtype_e))
     return SPARK_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int BH = B * H;
   float* Dws = static_cast<float*>(workspace);
-  SPARK_DISPATCH(launch_bwd, Q, K, V, O, LSE, dO, dQ, dK, dV, Dws, BH, N, scale, st, ev);
+  SPARK_DISPATCH(launch_bwd, Q, K, V, O, LSE, dO, dQ, dK, dV, Dws, BH, Nq, Nk, scale, st, ev);
 }
 
 int spark_mha_bwd(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
                   const void* dO, void* dQ, void* dK, void* dV, void* workspace,
                   size_t workspace_bytes, int B, int H, int N, int d, float scale, int causal,
                   spark_dtype_t dtype, void* stream) {
-  return bwd_impl(Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, B, H, N, d, scale,
-                  causal, dtype, stream, nullptr);
+  return bwd_impl(Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, B, H, N, N, d,
+                  scale, causal, dtype, stream, nullptr);
+}
+
+int spark_mha_cross_bwd(const void* Q, const void* K, const void* V, const void* O,
+                        const float* LSE, const void* dO, void* dQ, void* dK, void* dV,
+                        void* workspace, size_t workspace_bytes, int B, int H, int Nq, int Nk,
+                        int d, float scale, int causal, spark_dtype_t dtype, void* stream) {
+  return bwd_impl(Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, B, H, Nq, Nk, d,
+                  scale, causal, dtype, stream, nullptr);
 }
 
 int spark_mha_bwd_marked(const void* Q, const void* K, const void* V, const void* O,
@@ -177,15 +199,15 @@ int spark_mha_bwd_marked(const void* Q, const void* K, const void* V, const void
                          float scale, int causal, spark_dtype_t dtype, void* stream,
                          void* const events[4]) {
   if (!events || !events[0] || !events[1] || !events[2] || !events[3]) return SPARK_ERR_NULL;
-  return bwd_impl(Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, B, H, N, d, scale,
-                  causal, dtype, stream, events);
+  return bwd_impl(Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, B, H, N, N, d,
+                  scale, causal, dtype, stream, events);
 }
 
 const char* spark_status_str(int status) {
   switch (status) {
     case SPARK_OK: return "ok";
     case SPARK_ERR_NULL: return "a required pointer is NULL";
-    case SPARK_ERR_SHAPE: return "unsupported shape or scale (need B,H,N >= 1, d in {64,128}, finite scale > 0)";
+    case SPARK_ERR_SHAPE: return "unsupported shape or scale (need B,H,N >= 1, d in {64,128}, finite scale > 0, Nq == Nk if causal)";
     case SPARK_ERR_DTYPE: return "unsupported dtype (need SPARK_F16 or SPARK_BF16)";
     case SPARK_ERR_ALIGN: return "a pointer is not 16-byte aligned";
     case SPARK_ERR_WORKSPACE: return "workspace smaller than spark_mha_bwd_workspace_bytes()";

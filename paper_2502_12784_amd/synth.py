@@ -86,8 +86,12 @@ def bits_to_f64(bits: np.ndarray, dtype: str) -> np.ndarray:
     raise ValueError(dtype)
 
 
-def make_inputs(B, H, N, d, dtype, seed, sigma_qk=1.0, sigma_v=1.0, sigma_do=1.0, heads=None):
+def make_inputs(B, H, N, d, dtype, seed, sigma_qk=1.0, sigma_v=1.0, sigma_do=1.0, heads=None,
+                Nk=None):
     """Return {"Q","K","V","dO"} -> uint16 arrays [B,H,N,d] (bit patterns).
+
+    ``Nk``: number of key/value rows if it differs from the N query rows
+    (cross-attention); K and V are then [B,H,Nk,d].
 
     ``heads``: optional list of flat (b*H+h) indices; if given, only those heads
     are returned (shape [len(heads),1,N,d]) but drawn exactly as in the full
@@ -98,12 +102,13 @@ def make_inputs(B, H, N, d, dtype, seed, sigma_qk=1.0, sigma_v=1.0, sigma_do=1.0
     out = {}
     for name, child in zip(("Q", "K", "V", "dO"), children):
         rng = np.random.default_rng(child)
-        x = rng.standard_normal((B * H, N, d), dtype=np.float32)
+        rows = Nk if (Nk is not None and name in ("K", "V")) else N
+        x = rng.standard_normal((B * H, rows, d), dtype=np.float32)
         if heads is not None:
             x = x[list(heads)]
-            x = x.reshape(len(heads), 1, N, d)
+            x = x.reshape(len(heads), 1, rows, d)
         else:
-            x = x.reshape(B, H, N, d)
+            x = x.reshape(B, H, rows, d)
         x = x * np.float32(sig[name])
         out[name] = round_to_bits(x, dtype)
     return out

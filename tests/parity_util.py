@@ -44,10 +44,15 @@ def to_f64(t) -> np.ndarray:
 def run_gpu(inp, dtype, scale, causal):
     """Forward then backward through the C ABI on the forward's own O and LSE."""
     import torch
-    from paper_2502_12784_amd import spark_mha_bwd, spark_mha_fwd
+    from paper_2502_12784_amd import (spark_mha_bwd, spark_mha_cross_bwd, spark_mha_cross_fwd,
+                                      spark_mha_fwd)
     Q, K, V, dO = (to_device(inp[n], dtype) for n in ("Q", "K", "V", "dO"))
-    O, LSE = spark_mha_fwd(Q, K, V, scale, causal)
-    dQ, dK, dV = spark_mha_bwd(Q, K, V, O, LSE, dO, scale, causal)
+    if K.shape != Q.shape:  # Nq != Nk: the cross-attention entry points
+        O, LSE = spark_mha_cross_fwd(Q, K, V, scale, causal)
+        dQ, dK, dV = spark_mha_cross_bwd(Q, K, V, O, LSE, dO, scale, causal)
+    else:
+        O, LSE = spark_mha_fwd(Q, K, V, scale, causal)
+        dQ, dK, dV = spark_mha_bwd(Q, K, V, O, LSE, dO, scale, causal)
     torch.cuda.synchronize()
     return {"O": O, "LSE": LSE, "dQ": dQ, "dK": dK, "dV": dV}
 

@@ -86,6 +86,33 @@ def test_bwd_validation(lib):
     assert _bwd(lib, fn="spark_mha_bwd_marked", extra=(evs,)) == E_NULL
 
 
+def test_cross_validation(lib):
+    def fwd(Nq=128, Nk=96, causal=0, **kw):
+        a = dict(q=0x1000, k=0x2000, v=0x3000, o=0x4000, lse=0x5000, B=1, H=1, d=64, scale=0.125, dtype=0)
+        a.update(kw)
+        return lib.spark_mha_cross_fwd(a["q"], a["k"], a["v"], a["o"], a["lse"], a["B"], a["H"], Nq, Nk,
+                                       a["d"], a["scale"], causal, a["dtype"], None)
+
+    def bwd(Nq=128, Nk=96, causal=0, ws_bytes=1 << 20, dk=0x8000):
+        return lib.spark_mha_cross_bwd(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000, dk, 0x9000,
+                                       0xA000, ws_bytes, 1, 1, Nq, Nk, 64, 0.125, causal, 0, None)
+
+    assert fwd(Nq=0) == E_SHAPE
+    assert fwd(Nk=0) == E_SHAPE
+    assert fwd(causal=1) == E_SHAPE               # causal needs Nq == Nk
+    assert fwd(Nk=1 << 25, d=128) == E_SHAPE      # Nk*d >= 2^31
+    assert fwd(v=None) == E_NULL
+    assert fwd(o=0x4002) == E_ALIGN
+    assert fwd(dtype=5) == E_DTYPE
+    assert bwd(causal=1) == E_SHAPE
+    assert bwd(Nk=0) == E_SHAPE
+    assert bwd(dk=None) == E_NULL
+    need = pkg.spark_mha_cross_bwd_workspace_bytes(1, 1, 128, 96, 64, 0)
+    assert need == 2 * 128 * 4                    # sized by the queries, not the keys
+    assert bwd(ws_bytes=need - 1) == E_WS
+    assert pkg.spark_mha_cross_bwd_workspace_bytes(1, 1, 128, 0, 64, 0) == 0
+
+
 def test_workspace_bytes(lib):
     assert pkg.spark_mha_bwd_workspace_bytes(4, 16, 4096, 128, 1) == 2 * 4 * 16 * 4096 * 4
     assert pkg.spark_mha_bwd_workspace_bytes(4, 16, 4096, 100, 1) == 0
