@@ -8,7 +8,9 @@ from .mha_oracle import (  # noqa: F401
     build,
     compile_source,
     default,
+    dropout_mask,
     mha_bwd,
     mha_fwd,
     num_threads,
+    philox4x32_10,
 )

@@ -24,16 +24,19 @@ def rng():
     return np.random.default_rng(20250212)
 
 
-def numpy_attention(Q, K, V, dO, scale, causal):
-    """Independent evaluation with library matmul / softmax / logsumexp."""
+def numpy_attention(Q, K, V, dO, scale, causal, keep=None, keep_scale=1.0):
+    """Independent evaluation with library matmul / softmax / logsumexp.  With a keep mask,
+    the dropped and rescaled probabilities Pd = keep_scale * keep * P replace P in O = Pd V,
+    and the chain rule through Pd gives dP = keep_scale * keep * (dO V^T)."""
     S = scale * Q @ np.swapaxes(K, -1, -2)
     if causal:
         S = np.where(np.tril(np.ones(S.shape[-2:], dtype=bool)), S, -np.inf)
     P = softmax(S, axis=-1)
     LSE = logsumexp(S, axis=-1)
-    O = P @ V
-    dV = np.swapaxes(P, -1, -2) @ dO
-    dP = dO @ np.swapaxes(V, -1, -2)
+    G = np.ones_like(P) if keep is None else keep_scale * keep.astype(np.float64)
+    O = (G * P) @ V
+    dV = np.swapaxes(G * P, -1, -2) @ dO
+    dP = G * (dO @ np.swapaxes(V, -1, -2))
     dS = P * (dP - (P * dP).sum(-1, keepdims=True))
     dQ = scale * dS @ K
     dK = scale * np.swapaxes(dS, -1, -2) @ Q
@@ -341,6 +344,128 @@ def check_rect_finite_difference_gradients(orc):
             assert err <= 1e-6, (name, err)
 
 
+def check_philox_known_answers(orc):
+    """The generator behind the dropout mask reproduces its published known-answer vectors."""
+    n = 0
+    with open(os.path.join(HERE, "golden", "philox4x32_10_kat.txt")) as f:
+        for line in f:
+            if not line.strip() or line.startswith("#"):
+                continue
+            w = [int(t, 16) for t in line.split()]
+            assert orc.philox4x32_10(w[0:4], w[4:6]) == w[6:10], line
+            n += 1
+    assert n == 3
+
+
+def check_dropout_mask_properties(orc):
+    """Drop rate threshold/256, dependence on seed/offset/head, independence of the problem
+    size (an entry's decision depends on its position only), and the stated byte layout."""
+    B, H, Nq, Nk = 2, 3, 70, 90
+    seed, offset = 0x123456789ABCDEF, 7
+    assert orc.dropout_mask(B, H, Nq, Nk, seed, offset, 0).all()            # threshold 0 keeps all
+    for thr in (26, 128, 230):
+        M = orc.dropout_mask(B, H, Nq, Nk, seed, offset, thr)
+        assert set(np.unique(M)) <= {0, 1}
+        n, p = M.size, thr / 256.0
+        assert abs((M == 0).mean() - p) <= 5 * math.sqrt(p * (1 - p) / n), thr
+        # rows and columns carry the same rate (no stuck byte lane)
+        for ax in (2, 3):
+            for r in range(4):
+                sl = M[:, :, r::4] if ax == 2 else M[:, :, :, r::4]
+                assert abs((sl == 0).mean() - p) <= 6 * math.sqrt(p * (1 - p) / sl.size), (thr, ax, r)
+    M = orc.dropout_mask(B, H, Nq, Nk, seed, offset, 128)
+    assert (M[0, 0] != M[0, 1]).mean() > 0.4 and (M[0, 0] != M[1, 0]).mean() > 0.4   # heads differ
+    assert (orc.dropout_mask(B, H, Nq, Nk, seed + 1, offset, 128) != M).mean() > 0.4
+    assert (orc.dropout_mask(B, H, Nq, Nk, seed + (1 << 32), offset, 128) != M).mean() > 0.4
+    assert (orc.dropout_mask(B, H, Nq, Nk, seed, offset + 1, 128) != M).mean() > 0.4
+    # monotone in the threshold: whatever is kept at a high drop rate is kept at a lower one
+    assert (orc.dropout_mask(B, H, Nq, Nk, seed, offset, 26) >= M).all()
+    # position only: a smaller problem sees the top-left corner of the larger one's mask,
+    # and heads are numbered b*H + h
+    small = orc.dropout_mask(1, 2, 33, 41, seed, offset, 128)
+    np.testing.assert_array_equal(small, M[:1, :2, :33, :41])
+    # the stated layout, evaluated entry by entry from the generator's words
+    for (h, i, j) in ((0, 0, 0), (0, 1, 2), (1, 5, 6), (4, 69, 89), (5, 34, 3), (3, 7, 88)):
+        x = orc.philox4x32_10([j // 4, i // 4, h, offset], [seed & 0xFFFFFFFF, seed >> 32])
+        u = (x[i % 4] >> (8 * (j % 4))) & 0xFF
+        assert M.reshape(B * H, Nq, Nk)[h, i, j] == (1 if u >= 128 else 0), (h, i, j)
+
+
+def check_dropout_against_numpy_scipy(orc):
+    r = rng()
+    for (Nq, Nk, causal) in ((33, 33, False), (33, 33, True), (20, 45, False)):
+        B, H, d, scale, thr = 1, 3, 8, 0.4, 77
+        keep = orc.dropout_mask(B, H, Nq, Nk, 99, 3, thr)
+        ks = 256.0 / (256 - thr)
+        Q, dO = r.standard_normal((B, H, Nq, d)) * 1.5, r.standard_normal((B, H, Nq, d))
+        K, V = r.standard_normal((B, H, Nk, d)) * 1.5, r.standard_normal((B, H, Nk, d))
+        ref = numpy_attention(Q, K, V, dO, scale, causal, keep, ks)
+        O, LSE, P = orc.mha_fwd(Q, K, V, scale, causal, return_P=True, keep=keep, keep_scale=ks)
+        g = orc.mha_bwd(Q, K, V, dO, scale, causal, keep=keep, keep_scale=ks)
+        np.testing.assert_allclose(P, ref["P"], rtol=1e-12, atol=1e-15)      # P itself: before dropout
+        np.testing.assert_allclose(LSE, ref["LSE"], rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(O, ref["O"], rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(g["O"], O, rtol=0, atol=0)
+        for name in ("dQ", "dK", "dV"):
+            np.testing.assert_allclose(g[name], ref[name], rtol=1e-11, atol=1e-13, err_msg=name)
+
+
+def check_dropout_degenerate_masks(orc):
+    """Keep everything with scale 1: no dropout.  Drop everything: O = 0 and all gradients 0."""
+    r = rng()
+    Q, K, V, dO = (r.standard_normal((1, 2, 17, 4)) for _ in range(4))
+    ones, zeros = np.ones((1, 2, 17, 17), np.uint8), np.zeros((1, 2, 17, 17), np.uint8)
+    for causal in (False, True):
+        a = orc.mha_bwd(Q, K, V, dO, 0.5, causal)
+        b = orc.mha_bwd(Q, K, V, dO, 0.5, causal, keep=ones, keep_scale=1.0)
+        for n in ("O", "LSE", "dQ", "dK", "dV"):
+            np.testing.assert_array_equal(a[n], b[n])
+        z = orc.mha_bwd(Q, K, V, dO, 0.5, causal, keep=zeros, keep_scale=2.0)
+        np.testing.assert_array_equal(z["LSE"], a["LSE"])
+        for n in ("O", "dQ", "dK", "dV"):
+            assert np.abs(z[n]).max() == 0.0, n
+
+
+def check_dropout_finite_difference_gradients(orc):
+    """With the mask held fixed, dQ, dK, dV are the gradient of L = sum(O * dO)."""
+    r = rng()
+    N, d, scale, h, thr = 6, 3, 0.6, 1e-5, 100
+    ks = 256.0 / (256 - thr)
+    for causal in (False, True):
+        keep = orc.dropout_mask(1, 1, N, N, 5, 0, thr)
+        assert 0 < keep.sum() < keep.size
+        Q, K, V, dO = (r.standard_normal((1, 1, N, d)) for _ in range(4))
+        g = orc.mha_bwd(Q, K, V, dO, scale, causal, keep=keep, keep_scale=ks)
+        base = [Q, K, V]
+        for name, idx in (("dQ", 0), ("dK", 1), ("dV", 2)):
+            num = np.zeros_like(Q)
+            for mi in np.ndindex(Q.shape):
+                ap, am = [a.copy() for a in base], [a.copy() for a in base]
+                ap[idx][mi] += h
+                am[idx][mi] -= h
+                lp = float((orc.mha_fwd(*ap, scale, causal, keep=keep, keep_scale=ks)[0] * dO).sum())
+                lm = float((orc.mha_fwd(*am, scale, causal, keep=keep, keep_scale=ks)[0] * dO).sum())
+                num[mi] = (lp - lm) / (2 * h)
+            err = np.abs(num - g[name]).max() / max(np.abs(g[name]).max(), 1e-30)
+            assert err <= 1e-6, (name, err)
+
+
+def check_dropout_is_unbiased(orc):
+    """Averaged over many masks, the dropped and rescaled O tends to the O without dropout
+    (survivors scaled by 256 / (256 - threshold))."""
+    r = rng()
+    N, d, thr, reps = 24, 4, 64, 600
+    Q, K, V = (r.standard_normal((1, 1, N, d)) for _ in range(3))
+    O0 = orc.mha_fwd(Q, K, V, 0.5, False)[0]
+    keep = orc.dropout_mask(1, reps, N, N, 2024, 0, thr)             # one mask per "head"
+    Qr, Kr, Vr = (np.broadcast_to(a, (1, reps, N, d)).copy() for a in (Q, K, V))
+    O = orc.mha_fwd(Qr, Kr, Vr, 0.5, False, keep=keep, keep_scale=256.0 / (256 - thr))[0]
+    # per-entry std of the estimate is at most sqrt(p/(1-p)) * max|V| * sqrt(sum P^2) / sqrt(reps)
+    tol = 5 * math.sqrt((thr / 256) / (1 - thr / 256)) * np.abs(V).max() / math.sqrt(reps)
+    assert np.abs(O.mean(1) - O0[:, 0]).max() <= tol
+    assert np.abs(O.mean(1) - O0[:, 0]).mean() <= 0.05 * np.abs(O0).mean() + 0.02
+
+
 CHECKS = [
     check_rows_of_P_sum_to_one,
     check_zero_Q_gives_uniform_attention,
@@ -360,6 +485,12 @@ CHECKS = [
     check_rect_finite_difference_gradients,
     check_rect_against_numpy_scipy,
     check_rect_causal_is_rejected,
+    check_philox_known_answers,
+    check_dropout_degenerate_masks,
+    check_dropout_finite_difference_gradients,
+    check_dropout_against_numpy_scipy,
+    check_dropout_is_unbiased,
+    check_dropout_mask_properties,
 ]
 
 
@@ -390,8 +521,8 @@ MISTAKES = {
     "dK without scale": ("for (int k = 0; k < d; ++k) dKj[k] *= scale;", ""),
     "dK from P instead of dS": ("dKj[k] += ds * Qh[(size_t)i * d + k];", "dKj[k] += p * Qh[(size_t)i * d + k];"),
     "dK with the wrong Q row": ("dKj[k] += ds * Qh[(size_t)i * d + k];", "dKj[k] += ds * Qh[(size_t)j * d + k];"),
-    "dV from dS instead of P": ("dVj[k] += p * dOh[(size_t)i * d + k];", "dVj[k] += ds * dOh[(size_t)i * d + k];"),
-    "dV transposed P": ("const double p = P[(size_t)i * Nk + j];\n        const double ds", "const double p = P[(size_t)j * Nk + i];\n        const double ds"),
+    "dV from dS instead of P": ("dVj[k] += pm * dOh[(size_t)i * d + k];", "dVj[k] += ds * dOh[(size_t)i * d + k];"),
+    "dV transposed P": ("const double p = P[(size_t)i * Nk + j];\n        const double pm", "const double p = P[(size_t)j * Nk + i];\n        const double pm"),
     "causal backward starts one row late": ("const int ibeg = causal ? j : 0;", "const int ibeg = causal ? j + 1 : 0;"),
     # mistakes that only a problem with Nq != Nk can show
     "dK/dV sum over Nk queries": ("for (int i = ibeg; i < Nq; ++i) {", "for (int i = ibeg; i < (Nq < Nk ? Nq : Nk); ++i) {"),
@@ -400,6 +531,22 @@ MISTAKES = {
     "dQ sums over the first Nq keys": ("const int jend = causal ? i + 1 : Nk;\n      for (int j = 0; j < jend; ++j) {\n        double dp",
                                        "const int jend = causal ? i + 1 : (Nq < Nk ? Nq : Nk);\n      for (int j = 0; j < jend; ++j) {\n        double dp"),
     "K and V of head h taken at the Q offset": ("*Kh = K + offk, *Vh = V + offk,", "*Kh = K + (Nq < Nk ? offq : offk), *Vh = V + (Nq < Nk ? offq : offk),"),
+    # mistakes in the dropout path and in the generator that draws the mask
+    "dropout: survivors not rescaled in O": ("p = keep[(size_t)i * Nk + j] ? r * p : 0.0;", "p = keep[(size_t)i * Nk + j] ? p : 0.0;"),
+    "dropout: dP not masked": ("        if (keeph) dp = keeph[(size_t)i * Nk + j] ? keep_scale * dp : 0.0;\n", ""),
+    "dropout: dP masked but not rescaled": ("dp = keeph[(size_t)i * Nk + j] ? keep_scale * dp : 0.0;", "dp = keeph[(size_t)i * Nk + j] ? dp : 0.0;"),
+    "dropout: dV from the undropped P": ("dVj[k] += pm * dOh[(size_t)i * d + k];", "dVj[k] += p * dOh[(size_t)i * d + k];"),
+    "dropout: dS from the dropped P": ("dS[(size_t)i * Nk + j] = P[(size_t)i * Nk + j] * (dp - Di);",
+                                       "dS[(size_t)i * Nk + j] = (keeph && !keeph[(size_t)i * Nk + j] ? 0.0 : P[(size_t)i * Nk + j]) * (dp - Di);"),
+    "philox: key not advanced": ("    k0 += 0x9E3779B9u;\n", ""),
+    "philox: multipliers swapped": ("const uint64_t p0 = (uint64_t)0xD2511F53u * c0;\n    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;",
+                                    "const uint64_t p0 = (uint64_t)0xCD9E8D57u * c0;\n    const uint64_t p1 = (uint64_t)0xD2511F53u * c2;"),
+    "philox: nine rounds": ("round < 10;", "round < 9;"),
+    "philox: output words in the wrong order": ("const uint32_t n1 = (uint32_t)p1;\n    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;\n    const uint32_t n3 = (uint32_t)p0;",
+                                                "const uint32_t n3 = (uint32_t)p1;\n    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;\n    const uint32_t n1 = (uint32_t)p0;"),
+    "mask: keep below the threshold": ("u >= (unsigned)threshold ? 1 : 0;", "u < (unsigned)threshold ? 1 : 0;"),
+    "mask: word and byte index exchanged": ("(x[i % 4] >> (8 * (j % 4)))", "(x[j % 4] >> (8 * (i % 4)))"),
+    "mask: head not in the counter": ("(uint32_t)(i / 4), (uint32_t)h, offset}", "(uint32_t)(i / 4), 0u, offset}"),
     "LSE_out rows strided by Nk": ("LSE_out[(size_t)h * Nq + i] = LSE[i];", "LSE_out[(size_t)h * (Nq < Nk ? Nq : Nk) + i] = LSE[i];"),
 }
 
