@@ -2,7 +2,8 @@
  * spark_mha.h -- C ABI of the fused multi-head-attention library for MI355X (gfx950).
  *
  * Two operations, each enqueued on a caller-provided HIP stream, each in a self-attention
- * form (one sequence length N) and a cross-attention form (Nq queries, Nk keys/values):
+ * form (one sequence length N), a cross-attention form (Nq queries, Nk keys/values) and a
+ * form with attention dropout:
  *
  *   spark_mha_fwd : O = softmax(scale * Q K^T [+ causal mask]) V, and the row
  *                   statistic LSE that the backward needs.
@@ -57,7 +58,7 @@ typedef enum {
   SPARK_OK = 0,
   SPARK_ERR_NULL = -1,      /* a required pointer is NULL */
   SPARK_ERR_SHAPE = -2,     /* B, H or N < 1; d not 64/128; a size limit exceeded; scale not
-                               finite or <= 0; causal with Nq != Nk */
+                               finite or <= 0; causal with Nq != Nk; invalid p_drop */
   SPARK_ERR_DTYPE = -3,     /* dtype is neither SPARK_F16 nor SPARK_BF16 */
   SPARK_ERR_ALIGN = -4,     /* a pointer is not 16-byte aligned */
   SPARK_ERR_WORKSPACE = -5, /* workspace too small (see spark_mha_bwd_workspace_bytes) */
@@ -143,6 +144,45 @@ int spark_mha_cross_bwd(const void* Q, const void* K, const void* V, const void*
                         void* workspace, size_t workspace_bytes,
                         int B, int H, int Nq, int Nk, int d, float scale, int causal,
                         spark_dtype_t dtype, void* stream);
+
+/*
+ * Attention dropout (paper Sec. 4.1: every measurement runs with a dropout rate of 0.1;
+ * Sec. 4.2: the backward applies the forward's dropout again so that the two agree).  The paper
+ * fixes neither where the mask acts nor how it is drawn; this library drops entries of P after
+ * the softmax, independently, and scales the survivors by 1/(1-p):
+ *   O = (r M o P) V,  dV = (r M o P)^T dO,  dP = r M o (dO V^T),  dS = P o (dP - D),
+ * with LSE unchanged.  The mask is never stored: every kernel regenerates it from
+ * (seed, offset).  The decision for (head h = b*H + head index, query i, key j) is
+ *   x = Philox4x32-10(counter = (j/4, i/4, h, offset), key = (seed & 0xffffffff, seed >> 32))
+ *   u = byte (j mod 4) of x[i mod 4] (byte 0 least significant);  keep iff u >= thr
+ * where thr = spark_dropout_threshold(p_drop) = floor(256 p_drop + 1/2): the rate is realised
+ * to 8 bits (0.1 -> 26/256), and r = 256 / (256 - thr) matches the realised rate exactly.
+ * p_drop must satisfy 0 <= p_drop and thr <= 255, else SPARK_ERR_SHAPE; thr = 0 runs the
+ * kernels without dropout.  A forward and its backward must be given the same
+ * (p_drop, seed, offset); use a new offset (or seed) for every attention call whose mask
+ * should differ.  Everything else is as for spark_mha_cross_fwd / spark_mha_cross_bwd.
+ */
+int spark_mha_dropout_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                          int B, int H, int Nq, int Nk, int d, float scale, int causal,
+                          float p_drop, unsigned long long seed, unsigned offset,
+                          spark_dtype_t dtype, void* stream);
+
+int spark_mha_dropout_bwd(const void* Q, const void* K, const void* V, const void* O,
+                          const float* LSE, const void* dO, void* dQ, void* dK, void* dV,
+                          void* workspace, size_t workspace_bytes,
+                          int B, int H, int Nq, int Nk, int d, float scale, int causal,
+                          float p_drop, unsigned long long seed, unsigned offset,
+                          spark_dtype_t dtype, void* stream);
+
+/* The 8-bit threshold a dropout rate is realised with (see above), or -1 if p_drop is invalid. */
+int spark_dropout_threshold(float p_drop);
+
+/*
+ * Writes the keep mask the dropout kernels use, for inspection and testing:
+ *   M : out, device, [B,H,Nq,Nk] bytes, 1 = keep, 0 = drop.  No alignment requirement.
+ */
+int spark_dropout_mask(unsigned char* M, int B, int H, int Nq, int Nk, float p_drop,
+                       unsigned long long seed, unsigned offset, void* stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char* spark_status_str(int status);

@@ -8,11 +8,15 @@ from .binding import (  # noqa: F401
     HipEvents,
     SparkError,
     load_library,
+    spark_dropout_mask,
+    spark_dropout_threshold,
     spark_mha_bwd,
     spark_mha_bwd_workspace_bytes,
     spark_mha_cross_bwd,
     spark_mha_cross_bwd_workspace_bytes,
     spark_mha_cross_fwd,
+    spark_mha_dropout_bwd,
+    spark_mha_dropout_fwd,
     spark_mha_fwd,
     status_str,
 )

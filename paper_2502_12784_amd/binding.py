@@ -18,7 +18,8 @@ SPARK_BF16 = 1
 
 EXPORTS = ("spark_mha_fwd", "spark_mha_bwd", "spark_mha_bwd_marked",
            "spark_mha_bwd_workspace_bytes", "spark_mha_cross_fwd", "spark_mha_cross_bwd",
-           "spark_mha_cross_bwd_workspace_bytes", "spark_status_str")
+           "spark_mha_cross_bwd_workspace_bytes", "spark_mha_dropout_fwd", "spark_mha_dropout_bwd",
+           "spark_dropout_threshold", "spark_dropout_mask", "spark_status_str")
 
 _lib = None
 
@@ -51,6 +52,16 @@ def load_library() -> ctypes.CDLL:
     lib.spark_mha_cross_bwd_workspace_bytes.argtypes = [i, i, i, i, i, i]
     lib.spark_mha_cross_bwd.restype = i
     lib.spark_mha_cross_bwd.argtypes = [vp] * 10 + [ctypes.c_size_t, i, i, i, i, i, f, i, i, vp]
+    u64, u32 = ctypes.c_uint64, ctypes.c_uint32
+    lib.spark_mha_dropout_fwd.restype = i
+    lib.spark_mha_dropout_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, f, i, f, u64, u32, i, vp]
+    lib.spark_mha_dropout_bwd.restype = i
+    lib.spark_mha_dropout_bwd.argtypes = ([vp] * 10 + [ctypes.c_size_t, i, i, i, i, i, f, i, f, u64,
+                                                      u32, i, vp])
+    lib.spark_dropout_threshold.restype = i
+    lib.spark_dropout_threshold.argtypes = [f]
+    lib.spark_dropout_mask.restype = i
+    lib.spark_dropout_mask.argtypes = [vp, i, i, i, i, f, u64, u32, vp]
     lib.spark_mha_bwd_marked.restype = i
     lib.spark_mha_bwd_marked.argtypes = lib.spark_mha_bwd.argtypes + [ctypes.POINTER(vp)]
     lib.spark_status_str.restype = ctypes.c_char_p
@@ -116,8 +127,23 @@ def spark_mha_cross_bwd_workspace_bytes(B: int, H: int, Nq: int, Nk: int, d: int
     return int(load_library().spark_mha_cross_bwd_workspace_bytes(B, H, Nq, Nk, d, dtype_code))
 
 
-def spark_mha_cross_fwd(Q, K, V, scale: float, causal: bool = False, O=None, LSE=None):
-    """O, LSE for Q [B,H,Nq,d] attending to K, V [B,H,Nk,d] (Nq and Nk may differ)."""
+def spark_dropout_threshold(p_drop: float) -> int:
+    return int(load_library().spark_dropout_threshold(float(p_drop)))
+
+
+def spark_dropout_mask(B: int, H: int, Nq: int, Nk: int, p_drop: float, seed: int, offset: int,
+                       device="cuda"):
+    """The keep mask [B,H,Nq,Nk] (uint8, 1 = keep) that the dropout kernels regenerate."""
+    import torch
+    M = torch.empty((B, H, Nq, Nk), dtype=torch.uint8, device=device)
+    _check(load_library().spark_dropout_mask(M.data_ptr(), B, H, Nq, Nk, float(p_drop), int(seed),
+                                             int(offset), _stream_ptr()))
+    return M
+
+
+def spark_mha_cross_fwd(Q, K, V, scale: float, causal: bool = False, O=None, LSE=None, dropout=None):
+    """O, LSE for Q [B,H,Nq,d] attending to K, V [B,H,Nk,d] (Nq and Nk may differ).
+    dropout: None, or (p_drop, seed, offset) -> spark_mha_dropout_fwd."""
     import torch
     lib = load_library()
     B, H, Nq, d = Q.shape
@@ -131,15 +157,36 @@ def spark_mha_cross_fwd(Q, K, V, scale: float, causal: bool = False, O=None, LSE
         LSE = torch.empty((B, H, Nq), dtype=torch.float32, device=Q.device)
     _require(O, (B, H, Nq, d), Q.dtype, "O")
     _require(LSE, (B, H, Nq), torch.float32, "LSE")
-    _check(lib.spark_mha_cross_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
-                                   LSE.data_ptr(), B, H, Nq, Nk, d, float(scale),
-                                   int(bool(causal)), _dtype_code(Q), _stream_ptr()))
+    if dropout is None:
+        _check(lib.spark_mha_cross_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                                       LSE.data_ptr(), B, H, Nq, Nk, d, float(scale),
+                                       int(bool(causal)), _dtype_code(Q), _stream_ptr()))
+    else:
+        p_drop, seed, offset = dropout
+        _check(lib.spark_mha_dropout_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                                         LSE.data_ptr(), B, H, Nq, Nk, d, float(scale),
+                                         int(bool(causal)), float(p_drop), int(seed), int(offset),
+                                         _dtype_code(Q), _stream_ptr()))
     return O, LSE
 
 
+def spark_mha_dropout_fwd(Q, K, V, scale: float, causal: bool, p_drop: float, seed: int,
+                          offset: int, O=None, LSE=None):
+    """Forward with attention dropout; the mask is a function of (p_drop, seed, offset)."""
+    return spark_mha_cross_fwd(Q, K, V, scale, causal, O, LSE, dropout=(p_drop, seed, offset))
+
+
+def spark_mha_dropout_bwd(Q, K, V, O, LSE, dO, scale: float, causal: bool, p_drop: float,
+                          seed: int, offset: int, dQ=None, dK=None, dV=None, workspace=None):
+    """Backward of spark_mha_dropout_fwd; pass the same (p_drop, seed, offset)."""
+    return spark_mha_cross_bwd(Q, K, V, O, LSE, dO, scale, causal, dQ, dK, dV, workspace,
+                               dropout=(p_drop, seed, offset))
+
+
 def spark_mha_cross_bwd(Q, K, V, O, LSE, dO, scale: float, causal: bool = False, dQ=None,
-                        dK=None, dV=None, workspace=None):
-    """dQ [B,H,Nq,d], dK, dV [B,H,Nk,d] for the problem of spark_mha_cross_fwd."""
+                        dK=None, dV=None, workspace=None, dropout=None):
+    """dQ [B,H,Nq,d], dK, dV [B,H,Nk,d] for the problem of spark_mha_cross_fwd.
+    dropout: None, or (p_drop, seed, offset) -> spark_mha_dropout_bwd."""
     import torch
     lib = load_library()
     B, H, Nq, d = Q.shape
@@ -160,10 +207,15 @@ def spark_mha_cross_bwd(Q, K, V, O, LSE, dO, scale: float, causal: bool = False,
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
     wbytes = workspace.numel() * workspace.element_size()
-    _check(lib.spark_mha_cross_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
-                                   LSE.data_ptr(), dO.data_ptr(), dQ.data_ptr(), dK.data_ptr(),
-                                   dV.data_ptr(), workspace.data_ptr(), wbytes, B, H, Nq, Nk, d,
-                                   float(scale), int(bool(causal)), code, _stream_ptr()))
+    ptrs = [Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(), dO.data_ptr(),
+            dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), workspace.data_ptr(), wbytes]
+    if dropout is None:
+        _check(lib.spark_mha_cross_bwd(*ptrs, B, H, Nq, Nk, d, float(scale), int(bool(causal)), code,
+                                       _stream_ptr()))
+    else:
+        p_drop, seed, offset = dropout
+        _check(lib.spark_mha_dropout_bwd(*ptrs, B, H, Nq, Nk, d, float(scale), int(bool(causal)),
+                                         float(p_drop), int(seed), int(offset), code, _stream_ptr()))
     return dQ, dK, dV
 
 

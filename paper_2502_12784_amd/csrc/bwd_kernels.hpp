@@ -25,6 +25,7 @@
 // is transposed as in the forward (lane = query column), so LSE_i and D_i are per-lane
 // scalars and dS^T is directly the B operand of dQ^T = K^T dS^T.
 #pragma once
+#include "dropout_gfx950.hpp"
 #include "mma_gfx950.hpp"
 #include "tiles_gfx950.hpp"
 
@@ -40,7 +41,8 @@ __global__ __launch_bounds__(256) void mha_bwd_dot_kernel(const T* __restrict__ 
                                                          const T* __restrict__ dO,
                                                          const float* __restrict__ LSE,
                                                          float* __restrict__ Dout,
-                                                         float* __restrict__ LSE2out, int64_t rows) {
+                                                         float* __restrict__ LSE2out, int64_t rows,
+                                                         float dscale) {
   using v8 = typename Frag<T>::v8;
   constexpr int CPR = D / 8;
   const int64_t chunk = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -55,7 +57,7 @@ __global__ __launch_bounds__(256) void mha_bwd_dot_kernel(const T* __restrict__ 
 #pragma unroll
   for (int off = CPR / 2; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
   if (row < rows && (threadIdx.x % CPR) == 0) {
-    Dout[row] = acc;
+    Dout[row] = acc * dscale;  // dscale = 1, or the keep probability under dropout (see dS there)
     LSE2out[row] = LSE[row] * 1.4426950408889634f;  // the backward kernels exponentiate in base 2
   }
 }
@@ -79,11 +81,12 @@ template <int D> struct BwdKvCfg {
   static_assert(4 * 32 * OSTR <= SMEM, "epilogue staging must fit");
 };
 
-template <typename T, int D, bool CAUSAL>
+template <typename T, int D, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Dws,
-    T* __restrict__ dK, T* __restrict__ dV, int Nq, int Nk, int nkt, float scale, float scale_log2) {
+    T* __restrict__ dK, T* __restrict__ dV, int Nq, int Nk, int nkt, float scale, float scale_log2,
+    Dropout dr) {
   using F = Frag<T>;
   using v8 = typename F::v8;
   using C = BwdKvCfg<D>;
@@ -198,13 +201,21 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_kernel(
         };
         load_agroup(0);
         f32x16 s, dp;
+        // Dropout: dS = P o (r M o dPraw - D) = r P o (M o dPraw - D (1-p)); the workspace holds
+        // D (1-p), the factor r goes into the final scale of dK, and -D (1-p) is added after the
+        // mask instead of seeding the accumulator.
+        float negd[16];
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) {
           const int o = stat_off + (sub * 32 + 8 * r4) * 4;
           const f32x4 l4 = lds_read16<f32x4>(smem, o);
           const f32x4 d4 = lds_read16<f32x4>(smem, o + C::BM * 4);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) { s[r4 * 4 + e] = l4[e]; dp[r4 * 4 + e] = d4[e]; }
+          for (int e = 0; e < 4; ++e) {
+            s[r4 * 4 + e] = l4[e];
+            dp[r4 * 4 + e] = DROP ? 0.f : d4[e];
+            negd[r4 * 4 + e] = d4[e];
+          }
         }
         load_agroup(1);
         sched_fence();
@@ -239,12 +250,20 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_kernel(
 
         float p[16], ds[16];
         const bool need_mask = CAUSAL && q0s < k0w + 31;
+        uint32_t kb[4];
+        if (DROP) keep_bytes_key_lane(dr, head, krow, q0s, lane, kb);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           float pe = __builtin_amdgcn_exp2f(s[r] * scale_log2);
           if (need_mask && krow > q0s + 8 * (r / 4) + 4 * g + (r % 4)) pe = 0.f;
-          p[r] = pe;
-          ds[r] = pe * dp[r];
+          if (DROP) {
+            const bool keep = keep_reg(kb, r, dr.thr);
+            p[r] = keep ? pe : 0.f;
+            ds[r] = pe * ((keep ? dp[r] : 0.f) + negd[r]);
+          } else {
+            p[r] = pe;
+            ds[r] = pe * dp[r];
+          }
         }
         v8 pf[2], dsf[2];
 #pragma unroll
@@ -281,8 +300,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_kernel(
     }
 
     SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
-    store_transposed<T, D, C::OSTR>(dk, scale, ob, dK + head_off_k, k0w, Nk, lane);
-    store_transposed<T, D, C::OSTR>(dv, 1.0f, ob, dV + head_off_k, k0w, Nk, lane);
+    store_transposed<T, D, C::OSTR>(dk, DROP ? scale * dr.rescale : scale, ob, dK + head_off_k, k0w, Nk, lane);
+    store_transposed<T, D, C::OSTR>(dv, DROP ? dr.rescale : 1.0f, ob, dV + head_off_k, k0w, Nk, lane);
   }  // rep
 }
 
@@ -315,11 +334,11 @@ template <int D> struct BwdKvPipeCfg {
   static_assert(4 * 32 * OSTR <= SLOTS * STAGE, "epilogue staging must fit");
 };
 
-template <typename T, int D, bool CAUSAL>
+template <typename T, int D, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ dO, const float* __restrict__ LSE2, const float* __restrict__ Dws,
-    T* __restrict__ dK, T* __restrict__ dV, int Nq, int Nk, int nkt, float scale) {
+    T* __restrict__ dK, T* __restrict__ dV, int Nq, int Nk, int nkt, float scale, Dropout dr) {
   using F = Frag<T>;
   using v8 = typename F::v8;
   using C = BwdKvPipeCfg<D>;
@@ -432,14 +451,24 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
 
     // One element of P and dS from finished scores: the unit of VALU work that is placed between
     // MFMAs.  r8 = register index within the half (0..7).
+    // Under dropout (kb: the step's decision bytes) the dV operand is the dropped P, and
+    // dS = r P o (M o dPraw - D (1-p)): the workspace holds D (1-p), r goes into the final scales.
     auto softmax_elem = [&](const f32x16& s, const f32x16& dp, int half, int r8, const f32x4 (&l)[2],
-                            const f32x4 (&d)[2], int q0s, bool mask, float* p, float* ds) {
+                            const f32x4 (&d)[2], int q0s, bool mask, const uint32_t (&kb)[4], float* p,
+                            float* ds) {
       const int r = 8 * half + r8;
       float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, -l[r8 >> 2][r8 & 3]));
       if (mask) pe = krow > q0s + 8 * (r / 4) + 4 * g + (r % 4) ? 0.f : pe;
-      p[r8] = pe;
-      ds[r8] = pe * (dp[r] - d[r8 >> 2][r8 & 3]);
+      if (DROP) {
+        const bool keep = keep_reg(kb, r, dr.thr);
+        p[r8] = keep ? pe : 0.f;
+        ds[r8] = pe * ((keep ? dp[r] : 0.f) - d[r8 >> 2][r8 & 3]);
+      } else {
+        p[r8] = pe;
+        ds[r8] = pe * (dp[r] - d[r8 >> 2][r8 & 3]);
+      }
     };
+    uint32_t kbCur[4] = {0, 0, 0, 0}, kbNew[4] = {0, 0, 0, 0};  // decision bytes of the current / next step
 
     // ---- prologue: stages s_begin and s_begin+1 resident, scores of the first step formed ----
     fetch_stage(s_begin, 0);
@@ -480,8 +509,9 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
     v8 pfL, dsfL;
     {
       float p[8], ds[8];
+      if (DROP) keep_bytes_key_lane(dr, head, krow, s_begin * C::BM, lane, kbCur);
 #pragma unroll
-      for (int r = 0; r < 8; ++r) softmax_elem(sV, dpV, 0, r, lL, dL, s_begin * C::BM, CAUSAL, p, ds);
+      for (int r = 0; r < 8; ++r) softmax_elem(sV, dpV, 0, r, lL, dL, s_begin * C::BM, CAUSAL, kbCur, p, ds);
       pfL = pack8<T>(p);
       dsfL = pack8<T>(ds);
     }
@@ -501,6 +531,7 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
       auto step = [&](f32x16& s_new, f32x16& dp_new, int sub_new, int q0_new, int sub_cur, int q0_cur) {
         // ---- region 1: scores of the next step  ||  second half of P, dS of the current step ----
         float p[8], ds[8];
+        if (DROP) keep_bytes_key_lane(dr, head, krow, q0_new, lane, kbNew);
         load_stats(lL, dL, sub_new, 0);
         load_tgroup(0, sub_cur);
 #pragma unroll
@@ -512,7 +543,7 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
             dp_new = F::mfma(fa[gi & 1][2 * e + 1], vf[2 * gi + e], dp_new);
           if ((i & 3) == 3 && gi + 2 < NG) load_agroup(gi + 2, sub_new);
           if (i == 2 * NG) load_tgroup(1, sub_cur);
-          if (i & 1) softmax_elem(sV, dpV, 1, i / 2, lH, dH, q0_cur, mask, p, ds);
+          if (i & 1) softmax_elem(sV, dpV, 1, i / 2, lH, dH, q0_cur, mask, kbCur, p, ds);
           sched_fence();
         }
         const v8 pfH = pack8<T>(p), dsfH = pack8<T>(ds);
@@ -530,8 +561,8 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
           for (int e = 0; e < 2; ++e) {
             dv[dt0 + e] = F::mfma(ft[tg & 1][2 * e], kk ? pfH : pfL, dv[dt0 + e]);
             dk[dt0 + e] = F::mfma(ft[tg & 1][2 * e + 1], kk ? dsfH : dsfL, dk[dt0 + e]);
-            softmax_elem(sV, dpV, 0, (8 / NTG) * tg + e, lL, dL, q0_new, mask, p, ds);
-            if (8 / NTG > 2) softmax_elem(sV, dpV, 0, (8 / NTG) * tg + 2 + e, lL, dL, q0_new, mask, p, ds);
+            softmax_elem(sV, dpV, 0, (8 / NTG) * tg + e, lL, dL, q0_new, mask, kbNew, p, ds);
+            if (8 / NTG > 2) softmax_elem(sV, dpV, 0, (8 / NTG) * tg + 2 + e, lL, dL, q0_new, mask, kbNew, p, ds);
             sched_fence();
           }
           if (tg + 2 < NTG) load_tgroup(tg + 2, sub_cur);
@@ -542,6 +573,10 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
         // materialise here: otherwise this arithmetic sinks to its use in the next step and
         // runs there with no MFMA to hide it
         asm volatile("" : "+v"(pfL), "+v"(dsfL));
+        if (DROP) {
+#pragma unroll
+          for (int a = 0; a < 4; ++a) kbCur[a] = kbNew[a];
+        }
       };
 
       // (m, 1) scores  ||  (m, 0) softmax; then (m, 0) dV / dK
@@ -579,8 +614,8 @@ __global__ __launch_bounds__(256, 1) void mha_bwd_dkdv_pipe_kernel(
     }
 
     SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
-    store_transposed<T, D, C::OSTR>(dk, scale, ob, dK + head_off_k, k0w, Nk, lane);
-    store_transposed<T, D, C::OSTR>(dv, 1.0f, ob, dV + head_off_k, k0w, Nk, lane);
+    store_transposed<T, D, C::OSTR>(dk, DROP ? scale * dr.rescale : scale, ob, dK + head_off_k, k0w, Nk, lane);
+    store_transposed<T, D, C::OSTR>(dv, DROP ? dr.rescale : 1.0f, ob, dV + head_off_k, k0w, Nk, lane);
   }  // rep
 }
 
@@ -600,11 +635,11 @@ template <int D> struct BwdQCfg {
   static_assert((STAGE & (STAGE - 1)) == 0, "XOR buffer switch");
 };
 
-template <typename T, int D, bool CAUSAL>
+template <typename T, int D, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Dws,
-    T* __restrict__ dQ, int Nq, int Nk, int nqt, float scale, float scale_log2) {
+    T* __restrict__ dQ, int Nq, int Nk, int nqt, float scale, float scale_log2, Dropout dr) {
   using F = Frag<T>;
   using v8 = typename F::v8;
   using C = BwdQCfg<D>;
@@ -728,8 +763,12 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
 
         float ds[16 * MT];
         const bool need_mask = (CAUSAL && k0 + C::BN - 1 > q0) || (k0 + C::BN > Nk);
+        // Dropout: dS = r P o (M o dPraw - D (1-p)); the workspace holds D (1-p) and the factor r
+        // goes into the final scale of dQ.
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+        for (int mt = 0; mt < MT; ++mt) {
+          uint32_t kb[4];
+          if (DROP) keep_bytes_query_lane(dr, head, qrow, k0 + 32 * mt, lane, kb);
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mt][r], scale_log2, -lse2));
@@ -738,8 +777,10 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
               const bool ok = key < Nk && (!CAUSAL || key <= qrow);
               if (!ok) pe = 0.f;
             }
-            ds[mt * 16 + r] = pe * (dp[mt][r] - Dq);
+            const float dpe = DROP && !keep_reg(kb, r, dr.thr) ? 0.f : dp[mt][r];
+            ds[mt * 16 + r] = pe * (dpe - Dq);
           }
+        }
         v8 dsf[NKK];
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) dsf[kk] = pack8<T>(&ds[kk * 8]);
@@ -768,7 +809,7 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
     }
 
     SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
-    store_transposed<T, D, C::OSTR>(dq, scale, ob, dQ + head_off, q0, Nq, lane);
+    store_transposed<T, D, C::OSTR>(dq, DROP ? scale * dr.rescale : scale, ob, dQ + head_off, q0, Nq, lane);
   }  // rep
 }
 

@@ -28,6 +28,7 @@
 //     wholly above their rows, and a workgroup takes the complementary pair of query tiles
 //     (nqt-1-p, p) so every workgroup carries the same amount of work.
 #pragma once
+#include "dropout_gfx950.hpp"
 #include "mma_gfx950.hpp"
 #include "tiles_gfx950.hpp"
 
@@ -46,10 +47,11 @@ template <int D> struct FwdCfg {
   static_assert(4 * 32 * OSTR <= SMEM, "epilogue staging must fit in the K/V buffers");
 };
 
-template <typename T, int D, bool CAUSAL>
+template <typename T, int D, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
-    T* __restrict__ O, float* __restrict__ LSE, int Nq, int Nk, int nqt, float scale_log2) {
+    T* __restrict__ O, float* __restrict__ LSE, int Nq, int Nk, int nqt, float scale_log2,
+    Dropout dr) {
   using F = Frag<T>;
   using v8 = typename F::v8;
   using v4 = typename F::v4;
@@ -203,6 +205,15 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
           for (int r = 1; r < 16; ++r) mx = fmaxf(mx, t[h * 16 + r]);
           return half_pair_max(mx) * scale_log2;  // scale > 0 commutes with the maximum
         };
+        // Dropout acts on P after the row sums are taken: dropped entries become zero in the
+        // operand of O += P V; the survivors' factor 1/(1-p) is applied once, to O, at the end.
+        auto drop_half = [&](int h) {
+          uint32_t kb[4];
+          keep_bytes_query_lane(dr, head, qrow, k0 + 32 * h, lane, kb);
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (!keep_reg(kb, r, dr.thr)) t[h * 16 + r] = 0.f;
+        };
         float rs = 0.f;
         auto exp_elem = [&](int i) {
           t[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(t[i], scale_log2, -m_run));
@@ -274,6 +285,7 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
           }
         }
         v8 pf[4];
+        if (DROP) drop_half(0);
         pf[0] = pack8<T>(&t[0]);
         pf[1] = pack8<T>(&t[8]);
         sched_fence();
@@ -292,6 +304,7 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
           sched_fence();
         }
         l_run += rs;
+        if (DROP) drop_half(1);
         pf[2] = pack8<T>(&t[16]);
         pf[3] = pack8<T>(&t[24]);
         sched_fence();
@@ -310,7 +323,7 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
 
     // Epilogue: normalise, round once, transpose through this wave's LDS slice, store rows.
     l_run = half_pair_sum(l_run);
-    const float inv = 1.0f / l_run;
+    const float inv = (DROP ? dr.rescale : 1.0f) / l_run;
     SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)

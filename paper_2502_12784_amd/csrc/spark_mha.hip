@@ -30,6 +30,25 @@ int check_common(int B, int H, int Nq, int Nk, int d, float scale, int causal, i
   return SPARK_OK;
 }
 
+// Dropout rate -> 8-bit threshold: an entry is dropped iff its random byte < thr, i.e. with
+// probability thr / 256.  -1 if the rate is not a number in [0, 255.5/256).
+int drop_threshold(float p_drop) {
+  if (!(p_drop >= 0.f) || !(p_drop < 1.f)) return -1;
+  const int thr = (int)floorf(p_drop * 256.0f + 0.5f);
+  return thr <= 255 ? thr : -1;
+}
+
+Dropout make_dropout(int thr, unsigned long long seed, unsigned offset) {
+  Dropout dr;
+  dr.key0 = (uint32_t)seed;
+  dr.key1 = (uint32_t)(seed >> 32);
+  dr.offset = offset;
+  dr.thr = (uint32_t)thr;
+  dr.keep_prob = (float)(256 - thr) / 256.0f;
+  dr.rescale = 256.0f / (float)(256 - thr);
+  return dr;
+}
+
 template <typename KernelT>
 int set_smem(KernelT kernel, int bytes) {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
@@ -37,25 +56,25 @@ int set_smem(KernelT kernel, int bytes) {
   return e == hipSuccess ? SPARK_OK : SPARK_ERR_LAUNCH;
 }
 
-template <typename T, int D, bool CAUSAL>
+template <typename T, int D, bool CAUSAL, bool DROP>
 int launch_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int BH, int Nq,
-               int Nk, float scale, hipStream_t st) {
+               int Nk, float scale, const Dropout& dr, hipStream_t st) {
   using C = FwdCfg<D>;
-  auto kernel = mha_fwd_kernel<T, D, CAUSAL>;
+  auto kernel = mha_fwd_kernel<T, D, CAUSAL, DROP>;
   static const int attr = set_smem(kernel, C::SMEM);
   if (attr != SPARK_OK) return attr;
   const int nqt = (Nq + C::BM - 1) / C::BM;
   const float scale_log2 = scale * 1.4426950408889634f;
   hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nqt))), dim3(256), C::SMEM, st,
                      static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
-                     static_cast<T*>(O), LSE, Nq, Nk, nqt, scale_log2);
+                     static_cast<T*>(O), LSE, Nq, Nk, nqt, scale_log2, dr);
   return hipGetLastError() == hipSuccess ? SPARK_OK : SPARK_ERR_LAUNCH;
 }
 
-template <typename T, int D, bool CAUSAL>
+template <typename T, int D, bool CAUSAL, bool DROP>
 int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
                const void* dO, void* dQ, void* dK, void* dV, float* Dws, int BH, int Nq, int Nk,
-               float scale, hipStream_t st, void* const* ev) {
+               float scale, const Dropout& dr, hipStream_t st, void* const* ev) {
   const T* q = static_cast<const T*>(Q);
   const T* k = static_cast<const T*>(K);
   const T* v = static_cast<const T*>(V);
@@ -74,78 +93,97 @@ int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const
     const int64_t rows = (int64_t)BH * Nq;
     const unsigned grid = (unsigned)((rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK);
     hipLaunchKernelGGL((mha_bwd_dot_kernel<T, D>), dim3(grid), dim3(256), 0, st, o, dout, LSE, Dws,
-                       LSE2ws, rows);
+                       LSE2ws, rows, DROP ? dr.keep_prob : 1.0f);
     if (hipGetLastError() != hipSuccess || !mark(1)) return SPARK_ERR_LAUNCH;
   }
   if constexpr (D == 128) {  // dK, dV: one workgroup per tile of 128 keys, software-pipelined
     using C = BwdKvPipeCfg<D>;
-    auto kernel = mha_bwd_dkdv_pipe_kernel<T, D, CAUSAL>;
+    auto kernel = mha_bwd_dkdv_pipe_kernel<T, D, CAUSAL, DROP>;
     static const int attr = set_smem(kernel, C::SMEM);
     if (attr != SPARK_OK) return attr;
     const int nkt = (Nk + C::BN - 1) / C::BN;
     hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nkt))), dim3(256), C::SMEM, st, q, k, v, dout,
-                       LSE2ws, Dws, static_cast<T*>(dK), static_cast<T*>(dV), Nq, Nk, nkt, scale);
+                       LSE2ws, Dws, static_cast<T*>(dK), static_cast<T*>(dV), Nq, Nk, nkt, scale, dr);
     if (hipGetLastError() != hipSuccess || !mark(2)) return SPARK_ERR_LAUNCH;
   } else {  // dK, dV: one workgroup per tile of 128 keys, two workgroups per CU
     using C = BwdKvCfg<D>;
-    auto kernel = mha_bwd_dkdv_kernel<T, D, CAUSAL>;
+    auto kernel = mha_bwd_dkdv_kernel<T, D, CAUSAL, DROP>;
     static const int attr = set_smem(kernel, C::SMEM);
     if (attr != SPARK_OK) return attr;
     const int nkt = (Nk + C::BN - 1) / C::BN;
     hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nkt))), dim3(256), C::SMEM, st, q, k, v, dout,
                        LSE, Dws, static_cast<T*>(dK), static_cast<T*>(dV), Nq, Nk, nkt, scale,
-                       scale_log2);
+                       scale_log2, dr);
     if (hipGetLastError() != hipSuccess || !mark(2)) return SPARK_ERR_LAUNCH;
   }
   {  // dQ: one workgroup per tile of 128 queries
     using C = BwdQCfg<D>;
-    auto kernel = mha_bwd_dq_kernel<T, D, CAUSAL>;
+    auto kernel = mha_bwd_dq_kernel<T, D, CAUSAL, DROP>;
     static const int attr = set_smem(kernel, C::SMEM);
     if (attr != SPARK_OK) return attr;
     const int nqt = (Nq + C::BM - 1) / C::BM;
     hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nqt))), dim3(256), C::SMEM, st, q, k, v, dout,
-                       LSE, Dws, static_cast<T*>(dQ), Nq, Nk, nqt, scale, scale_log2);
+                       LSE, Dws, static_cast<T*>(dQ), Nq, Nk, nqt, scale, scale_log2, dr);
     if (hipGetLastError() != hipSuccess || !mark(3)) return SPARK_ERR_LAUNCH;
   }
   return SPARK_OK;
 }
 
-// Expand the (dtype, d, causal) runtime triple into a template instantiation.
+// Expand the (dtype, d, causal, dropout) runtime tuple into a template instantiation.
+#define SPARK_DISPATCH_CD(FN, T, D, ...)                                               \
+  do {                                                                                 \
+    if (causal) return drop ? FN<T, D, true, true>(__VA_ARGS__)                        \
+                            : FN<T, D, true, false>(__VA_ARGS__);                      \
+    return drop ? FN<T, D, false, true>(__VA_ARGS__) : FN<T, D, false, false>(__VA_ARGS__); \
+  } while (0)
 #define SPARK_DISPATCH(FN, ...)                                                        \
   do {                                                                                 \
     if (dtype == SPARK_F16) {                                                          \
-      if (d == 64) return causal ? FN<_Float16, 64, true>(__VA_ARGS__)                 \
-                                 : FN<_Float16, 64, false>(__VA_ARGS__);               \
-      return causal ? FN<_Float16, 128, true>(__VA_ARGS__)                             \
-                    : FN<_Float16, 128, false>(__VA_ARGS__);                           \
+      if (d == 64) SPARK_DISPATCH_CD(FN, _Float16, 64, __VA_ARGS__);                   \
+      SPARK_DISPATCH_CD(FN, _Float16, 128, __VA_ARGS__);                               \
     }                                                                                  \
-    if (d == 64) return causal ? FN<__bf16, 64, true>(__VA_ARGS__)                     \
-                               : FN<__bf16, 64, false>(__VA_ARGS__);                   \
-    return causal ? FN<__bf16, 128, true>(__VA_ARGS__)                                 \
-                  : FN<__bf16, 128, false>(__VA_ARGS__);                               \
+    if (d == 64) SPARK_DISPATCH_CD(FN, __bf16, 64, __VA_ARGS__);                       \
+    SPARK_DISPATCH_CD(FN, __bf16, 128, __VA_ARGS__);                                   \
   } while (0)
 
 }  // namespace
 
 extern "C" {
 
-int spark_mha_cross_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
-                        int H, int Nq, int Nk, int d, float scale, int causal,
-                        spark_dtype_t dtype_e, void* stream) {
+static int fwd_impl(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H,
+                    int Nq, int Nk, int d, float scale, int causal, int thr,
+                    unsigned long long seed, unsigned offset, spark_dtype_t dtype_e, void* stream) {
   const int dtype = (int)dtype_e;
   if (!Q || !K || !V || !O || !LSE) return SPARK_ERR_NULL;
   const int rc = check_common(B, H, Nq, Nk, d, scale, causal, dtype);
   if (rc != SPARK_OK) return rc;
+  if (thr < 0) return SPARK_ERR_SHAPE;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE))
     return SPARK_ERR_ALIGN;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int BH = B * H;
-  SPARK_DISPATCH(launch_fwd, Q, K, V, O, LSE, BH, Nq, Nk, scale, st);
+  const bool drop = thr > 0;
+  const Dropout dr = make_dropout(thr, seed, offset);
+  SPARK_DISPATCH(launch_fwd, Q, K, V, O, LSE, BH, Nq, Nk, scale, dr, st);
 }
 
 int spark_mha_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H,
                   int N, int d, float scale, int causal, spark_dtype_t dtype, void* stream) {
-  return spark_mha_cross_fwd(Q, K, V, O, LSE, B, H, N, N, d, scale, causal, dtype, stream);
+  return fwd_impl(Q, K, V, O, LSE, B, H, N, N, d, scale, causal, 0, 0, 0, dtype, stream);
+}
+
+int spark_mha_cross_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
+                        int H, int Nq, int Nk, int d, float scale, int causal,
+                        spark_dtype_t dtype, void* stream) {
+  return fwd_impl(Q, K, V, O, LSE, B, H, Nq, Nk, d, scale, causal, 0, 0, 0, dtype, stream);
+}
+
+int spark_mha_dropout_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
+                          int H, int Nq, int Nk, int d, float scale, int causal, float p_drop,
+                          unsigned long long seed, unsigned offset, spark_dtype_t dtype,
+                          void* stream) {
+  return fwd_impl(Q, K, V, O, LSE, B, H, Nq, Nk, d, scale, causal, drop_threshold(p_drop), seed,
+                  offset, dtype, stream);
 }
 
 size_t spark_mha_cross_bwd_workspace_bytes(int B, int H, int Nq, int Nk, int d,
@@ -161,11 +199,13 @@ size_t spark_mha_bwd_workspace_bytes(int B, int H, int N, int d, spark_dtype_t d
 static int bwd_impl(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
                     const void* dO, void* dQ, void* dK, void* dV, void* workspace,
                     size_t workspace_bytes, int B, int H, int Nq, int Nk, int d, float scale,
-                    int causal, spark_dtype_t dtype_e, void* stream, void* const* ev) {
+                    int causal, int thr, unsigned long long seed, unsigned offset,
+                    spark_dtype_t dtype_e, void* stream, void* const* ev) {
   const int dtype = (int)dtype_e;
   if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV || !workspace) return SPARK_ERR_NULL;
   const int rc = check_common(B, H, Nq, Nk, d, scale, causal, dtype);
   if (rc != SPARK_OK) return rc;
+  if (thr < 0) return SPARK_ERR_SHAPE;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE) ||
       !aligned16(dO) || !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
     return SPARK_ERR_ALIGN;
@@ -174,7 +214,9 @@ static int bwd_impl(const void* Q, const void* K, const void* V, const void* O, 
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int BH = B * H;
   float* Dws = static_cast<float*>(workspace);
-  SPARK_DISPATCH(launch_bwd, Q, K, V, O, LSE, dO, dQ, dK, dV, Dws, BH, Nq, Nk, scale, st, ev);
+  const bool drop = thr > 0;
+  const Dropout dr = make_dropout(thr, seed, offset);
+  SPARK_DISPATCH(launch_bwd, Q, K, V, O, LSE, dO, dQ, dK, dV, Dws, BH, Nq, Nk, scale, dr, st, ev);
 }
 
 int spark_mha_bwd(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
@@ -182,7 +224,7 @@ int spark_mha_bwd(const void* Q, const void* K, const void* V, const void* O, co
                   size_t workspace_bytes, int B, int H, int N, int d, float scale, int causal,
                   spark_dtype_t dtype, void* stream) {
   return bwd_impl(Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, B, H, N, N, d,
-                  scale, causal, dtype, stream, nullptr);
+                  scale, causal, 0, 0, 0, dtype, stream, nullptr);
 }
 
 int spark_mha_cross_bwd(const void* Q, const void* K, const void* V, const void* O,
@@ -190,7 +232,16 @@ int spark_mha_cross_bwd(const void* Q, const void* K, const void* V, const void*
                         void* workspace, size_t workspace_bytes, int B, int H, int Nq, int Nk,
                         int d, float scale, int causal, spark_dtype_t dtype, void* stream) {
   return bwd_impl(Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, B, H, Nq, Nk, d,
-                  scale, causal, dtype, stream, nullptr);
+                  scale, causal, 0, 0, 0, dtype, stream, nullptr);
+}
+
+int spark_mha_dropout_bwd(const void* Q, const void* K, const void* V, const void* O,
+                          const float* LSE, const void* dO, void* dQ, void* dK, void* dV,
+                          void* workspace, size_t workspace_bytes, int B, int H, int Nq, int Nk,
+                          int d, float scale, int causal, float p_drop, unsigned long long seed,
+                          unsigned offset, spark_dtype_t dtype, void* stream) {
+  return bwd_impl(Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, B, H, Nq, Nk, d,
+                  scale, causal, drop_threshold(p_drop), seed, offset, dtype, stream, nullptr);
 }
 
 int spark_mha_bwd_marked(const void* Q, const void* K, const void* V, const void* O,
@@ -200,14 +251,31 @@ int spark_mha_bwd_marked(const void* Q, const void* K, const void* V, const void
                          void* const events[4]) {
   if (!events || !events[0] || !events[1] || !events[2] || !events[3]) return SPARK_ERR_NULL;
   return bwd_impl(Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, B, H, N, N, d,
-                  scale, causal, dtype, stream, events);
+                  scale, causal, 0, 0, 0, dtype, stream, events);
+}
+
+int spark_dropout_threshold(float p_drop) { return drop_threshold(p_drop); }
+
+int spark_dropout_mask(unsigned char* M, int B, int H, int Nq, int Nk, float p_drop,
+                       unsigned long long seed, unsigned offset, void* stream) {
+  if (!M) return SPARK_ERR_NULL;
+  if (B < 1 || H < 1 || Nq < 1 || Nk < 1) return SPARK_ERR_SHAPE;
+  const int thr = drop_threshold(p_drop);
+  if (thr < 0) return SPARK_ERR_SHAPE;
+  const int qblocks = (Nq + 3) / 4, kblocks = (Nk + 3) / 4;
+  const long long total = (long long)B * H * qblocks * kblocks;
+  if (total >= ((long long)1 << 31) * 256) return SPARK_ERR_SHAPE;
+  const unsigned grid = (unsigned)((total + 255) / 256);
+  hipLaunchKernelGGL(dropout_mask_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     M, Nq, Nk, qblocks, kblocks, total, make_dropout(thr, seed, offset));
+  return hipGetLastError() == hipSuccess ? SPARK_OK : SPARK_ERR_LAUNCH;
 }
 
 const char* spark_status_str(int status) {
   switch (status) {
     case SPARK_OK: return "ok";
     case SPARK_ERR_NULL: return "a required pointer is NULL";
-    case SPARK_ERR_SHAPE: return "unsupported shape or scale (need B,H,N >= 1, d in {64,128}, finite scale > 0, Nq == Nk if causal)";
+    case SPARK_ERR_SHAPE: return "unsupported shape or scale (need B,H,N >= 1, d in {64,128}, finite scale > 0, Nq == Nk if causal, 0 <= p_drop < 0.998)";
     case SPARK_ERR_DTYPE: return "unsupported dtype (need SPARK_F16 or SPARK_BF16)";
     case SPARK_ERR_ALIGN: return "a pointer is not 16-byte aligned";
     case SPARK_ERR_WORKSPACE: return "workspace smaller than spark_mha_bwd_workspace_bytes()";

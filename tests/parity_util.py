@@ -41,13 +41,17 @@ def to_f64(t) -> np.ndarray:
     return t.detach().to(torch.float64).cpu().numpy()
 
 
-def run_gpu(inp, dtype, scale, causal):
-    """Forward then backward through the C ABI on the forward's own O and LSE."""
+def run_gpu(inp, dtype, scale, causal, dropout=None):
+    """Forward then backward through the C ABI on the forward's own O and LSE.
+    dropout: None or (p_drop, seed, offset) for the dropout entry points."""
     import torch
     from paper_2502_12784_amd import (spark_mha_bwd, spark_mha_cross_bwd, spark_mha_cross_fwd,
-                                      spark_mha_fwd)
+                                      spark_mha_dropout_bwd, spark_mha_dropout_fwd, spark_mha_fwd)
     Q, K, V, dO = (to_device(inp[n], dtype) for n in ("Q", "K", "V", "dO"))
-    if K.shape != Q.shape:  # Nq != Nk: the cross-attention entry points
+    if dropout is not None:
+        O, LSE = spark_mha_dropout_fwd(Q, K, V, scale, causal, *dropout)
+        dQ, dK, dV = spark_mha_dropout_bwd(Q, K, V, O, LSE, dO, scale, causal, *dropout)
+    elif K.shape != Q.shape:  # Nq != Nk: the cross-attention entry points
         O, LSE = spark_mha_cross_fwd(Q, K, V, scale, causal)
         dQ, dK, dV = spark_mha_cross_bwd(Q, K, V, O, LSE, dO, scale, causal)
     else:
@@ -57,9 +61,19 @@ def run_gpu(inp, dtype, scale, causal):
     return {"O": O, "LSE": LSE, "dQ": dQ, "dK": dK, "dV": dV}
 
 
-def run_oracle(inp, dtype, scale, causal, heads=None):
-    """Oracle on all heads, or on the flat head indices `heads` of [B,H,N,d] bit arrays."""
+def run_oracle(inp, dtype, scale, causal, heads=None, dropout=None):
+    """Oracle on all heads, or on the flat head indices `heads` of [B,H,N,d] bit arrays.
+    dropout: None or (threshold, seed, offset); the oracle draws the keep mask itself."""
     arrs = {}
+    B, H, Nq, _ = inp["Q"].shape
+    Nk = inp["K"].shape[2]
+    keep, ks = None, 1.0
+    if dropout is not None:
+        thr, seed, offset = dropout
+        keep = oracle.dropout_mask(B, H, Nq, Nk, seed, offset, thr)
+        ks = 256.0 / (256 - thr)
+        if heads is not None:
+            keep = np.ascontiguousarray(keep.reshape(B * H, 1, Nq, Nk)[list(heads)])
     for n in ("Q", "K", "V", "dO"):
         a = inp[n]
         if heads is not None:
@@ -68,10 +82,10 @@ def run_oracle(inp, dtype, scale, causal, heads=None):
         arrs[n] = synth.bits_to_f64(a, dtype)
     # scale as the fp32 value the kernel receives
     s = float(np.float32(scale))
-    ref = oracle.mha_bwd(arrs["Q"], arrs["K"], arrs["V"], arrs["dO"], s, causal)
+    ref = oracle.mha_bwd(arrs["Q"], arrs["K"], arrs["V"], arrs["dO"], s, causal, keep, ks)
     if dtype == synth.BF16:  # bound on the effect of rounding P to bf16: 2^-9 * P |V|
         ref["O_operand_rounding"] = 2.0 ** -9 * oracle.mha_fwd(arrs["Q"], arrs["K"], np.abs(arrs["V"]),
-                                                               s, causal)[0]
+                                                               s, causal, False, keep, ks)[0]
     return ref
 
 

@@ -113,6 +113,35 @@ def test_cross_validation(lib):
     assert pkg.spark_mha_cross_bwd_workspace_bytes(1, 1, 128, 0, 64, 0) == 0
 
 
+def test_dropout_validation(lib):
+    assert pkg.spark_dropout_threshold(0.1) == 26      # the paper's rate, realised to 8 bits
+    assert pkg.spark_dropout_threshold(0.0) == 0
+    assert pkg.spark_dropout_threshold(255.4 / 256) == 255
+    assert pkg.spark_dropout_threshold(255.6 / 256) == -1
+    assert pkg.spark_dropout_threshold(-1e-3) == -1
+    assert pkg.spark_dropout_threshold(float("nan")) == -1
+
+    def fwd(p=0.1, q=0x1000, Nq=128, Nk=128, causal=0):
+        return lib.spark_mha_dropout_fwd(q, 0x2000, 0x3000, 0x4000, 0x5000, 1, 1, Nq, Nk, 64, 0.125, causal,
+                                         p, 1234, 0, 0, None)
+
+    def bwd(p=0.1, ws_bytes=1 << 20, Nk=128):
+        return lib.spark_mha_dropout_bwd(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000, 0x8000,
+                                         0x9000, 0xA000, ws_bytes, 1, 1, 128, Nk, 64, 0.125, 0, p, 1234, 0,
+                                         0, None)
+
+    assert fwd(p=1.0) == E_SHAPE
+    assert fwd(p=-0.1) == E_SHAPE
+    assert fwd(q=None) == E_NULL
+    assert fwd(Nk=64, causal=1) == E_SHAPE
+    assert bwd(p=float("nan")) == E_SHAPE
+    assert bwd(ws_bytes=8) == E_WS
+    assert bwd(Nk=0) == E_SHAPE
+    assert lib.spark_dropout_mask(None, 1, 1, 4, 4, 0.1, 1, 0, None) == E_NULL
+    assert lib.spark_dropout_mask(0x1000, 1, 1, 0, 4, 0.1, 1, 0, None) == E_SHAPE
+    assert lib.spark_dropout_mask(0x1000, 1, 1, 4, 4, 2.0, 1, 0, None) == E_SHAPE
+
+
 def test_workspace_bytes(lib):
     assert pkg.spark_mha_bwd_workspace_bytes(4, 16, 4096, 128, 1) == 2 * 4 * 16 * 4096 * 4
     assert pkg.spark_mha_bwd_workspace_bytes(4, 16, 4096, 100, 1) == 0

@@ -1,0 +1,123 @@
+"""GPU parity for attention dropout (paper Sec. 4.1: rate 0.1 in every measurement; Sec. 4.2:
+the backward repeats the forward's dropout).  The library regenerates the keep mask inside its
+kernels from (seed, offset); the oracle draws the same mask with its own implementation of the
+generator and applies it as an explicit array.  Same bar as the other parity tests; the mask
+itself is compared bit for bit.
+"""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2502_12784_amd import synth
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+SEED = 0x9E3779B97F4A7C15  # uses both key words
+
+
+def test_threshold_of_the_papers_rate():
+    from paper_2502_12784_amd import spark_dropout_threshold
+    assert spark_dropout_threshold(0.1) == 26
+    assert spark_dropout_threshold(0.0) == 0
+    assert spark_dropout_threshold(0.5) == 128
+    assert spark_dropout_threshold(0.999) == -1
+    assert spark_dropout_threshold(-0.1) == -1
+    assert spark_dropout_threshold(float("nan")) == -1
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 4, 4), (2, 3, 70, 90), (1, 2, 129, 31), (1, 1, 1, 257), (3, 1, 333, 1)])
+@pytest.mark.parametrize("p", [0.1, 0.5, 0.9])
+def test_mask_kernel_equals_oracle_mask(shape, p):
+    from paper_2502_12784_amd import spark_dropout_mask, spark_dropout_threshold
+    B, H, Nq, Nk = shape
+    thr = spark_dropout_threshold(p)
+    for seed, offset in ((SEED, 0), (1, 0xFFFFFFFF), (0, 5)):
+        M = spark_dropout_mask(B, H, Nq, Nk, p, seed, offset).cpu().numpy()
+        ref = oracle.dropout_mask(B, H, Nq, Nk, seed, offset, thr)
+        np.testing.assert_array_equal(M, ref)
+
+
+def _run(B, H, Nq, Nk, d, dtype, causal, p, seed=SEED, offset=3):
+    from paper_2502_12784_amd import spark_dropout_threshold
+    scale = 1.0 / math.sqrt(d)
+    inp = synth.make_inputs(B, H, Nq, d, dtype, seed=6000 + Nq + Nk + d, Nk=None if Nk == Nq else Nk)
+    print(f"\n[dropout] B={B} H={H} Nq={Nq} Nk={Nk} d={d} {dtype} causal={causal} p={p}", flush=True)
+    gpu = pu.run_gpu(inp, dtype, scale, causal, dropout=(p, seed, offset))
+    ref = pu.run_oracle(inp, dtype, scale, causal, dropout=(spark_dropout_threshold(p), seed, offset))
+    m = pu.compare(gpu, ref, dtype)
+    print(f"[dropout] {m}", flush=True)
+    return m
+
+
+SMALL = [(1, 2, 128, 64), (2, 2, 256, 128), (1, 3, 320, 64), (1, 2, 63, 128), (1, 2, 65, 64),
+         (1, 1, 200, 128), (1, 2, 333, 64), (1, 1, 777, 128), (2, 1, 1, 64)]
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+@pytest.mark.parametrize("shape", SMALL)
+def test_dropout_small_shapes_all_elements(shape, dtype, causal):
+    B, H, N, d = shape
+    m = _run(B, H, N, N, d, dtype, causal, 0.1)
+    pu.assert_within_tolerance(m, (shape, dtype, causal))
+
+
+@pytest.mark.parametrize("p", [0.5, 0.9])
+@pytest.mark.parametrize("d", [64, 128])
+def test_dropout_high_rates(d, p):
+    m = _run(1, 2, 300, 300, d, synth.F16, True, p)
+    pu.assert_within_tolerance(m, (d, p))
+
+
+@pytest.mark.parametrize("shape", [(1, 2, 200, 77, 64), (2, 2, 77, 200, 128), (1, 2, 129, 257, 64),
+                                   (1, 1, 640, 128, 128)])
+def test_dropout_with_unequal_lengths(shape):
+    B, H, Nq, Nk, d = shape
+    m = _run(B, H, Nq, Nk, d, synth.BF16, False, 0.1)
+    pu.assert_within_tolerance(m, shape)
+
+
+def test_zero_rate_is_the_plain_path_and_masks_depend_on_offset():
+    import torch
+    inp = synth.make_inputs(1, 2, 200, 64, synth.F16, seed=77)
+    plain = pu.run_gpu(inp, synth.F16, 0.125, True)
+    zero = pu.run_gpu(inp, synth.F16, 0.125, True, dropout=(0.0, SEED, 0))
+    a = pu.run_gpu(inp, synth.F16, 0.125, True, dropout=(0.1, SEED, 0))
+    a2 = pu.run_gpu(inp, synth.F16, 0.125, True, dropout=(0.1, SEED, 0))
+    b = pu.run_gpu(inp, synth.F16, 0.125, True, dropout=(0.1, SEED, 1))
+    for n in ("O", "LSE", "dQ", "dK", "dV"):
+        assert torch.equal(plain[n], zero[n]), n
+        assert torch.equal(a[n], a2[n]), n
+    assert torch.equal(a["LSE"], plain["LSE"])          # the softmax statistics ignore dropout
+    assert not torch.equal(a["O"], plain["O"])
+    assert not torch.equal(a["O"], b["O"])
+
+
+def test_invalid_rate_is_refused():
+    import torch
+    from paper_2502_12784_amd import SparkError, spark_mha_dropout_fwd
+    Q = torch.zeros(1, 1, 64, 64, dtype=torch.float16, device="cuda")
+    for p in (-0.5, 0.999, 1.0, float("nan")):
+        with pytest.raises(SparkError) as e:
+            spark_mha_dropout_fwd(Q, Q, Q, 0.125, False, p, 1, 0)
+        assert e.value.status == -2
+
+
+@pytest.mark.parametrize("name", ["C2", "C4"])
+def test_dropout_full_size_configs_sampled_heads(name):
+    """The paper's rate on two of the full-size configurations; two heads checked in full."""
+    from paper_2502_12784_amd import spark_dropout_threshold
+    w = synth.WORKLOADS[name]
+    inp = synth.make_workload_inputs(w)
+    gpu = pu.run_gpu(inp, w.dtype, w.scale, w.causal, dropout=(0.1, SEED, 11))
+    heads = [1, w.B * w.H - 1]
+    ref = pu.run_oracle(inp, w.dtype, w.scale, w.causal, heads=heads,
+                        dropout=(spark_dropout_threshold(0.1), SEED, 11))
+    m = pu.compare(gpu, ref, w.dtype, heads=heads)
+    print(f"\n[dropout] {name} heads={heads}: {m}", flush=True)
+    pu.assert_within_tolerance(m, name)
+    for n in ("O", "LSE", "dQ", "dK", "dV"):
+        assert np.isfinite(pu.to_f64(gpu[n])).all(), n
