@@ -40,9 +40,13 @@ def read_traffic(workload: str, kernel: str):
     return None
 
 
-def time_workload(w, steps, warmup):
+def time_workload(w, steps, warmup, dropout=None):
+    """Average ms per step (wall clock) and per kernel (HIP events on the launch stream).
+    dropout: None, or (p_drop, seed, offset): the dropout entry points; then the backward is
+    timed as a whole (key "bwd") instead of per kernel."""
     import torch
-    from paper_2502_12784_amd import HipEvents, spark_mha_bwd, spark_mha_fwd, synth
+    from paper_2502_12784_amd import (HipEvents, spark_mha_bwd, spark_mha_dropout_bwd,
+                                      spark_mha_dropout_fwd, spark_mha_fwd, synth)
     from paper_2502_12784_amd.binding import _dtype_code, spark_mha_bwd_workspace_bytes
 
     def dev(bits):
@@ -61,9 +65,18 @@ def time_workload(w, steps, warmup):
     def step(ev=None, base=0):
         if ev is not None:
             ev.record(base)
-        spark_mha_fwd(Q, K, V, w.scale, w.causal, O=O, LSE=LSE)
-        spark_mha_bwd(Q, K, V, O, LSE, dO, w.scale, w.causal, dQ=dQ, dK=dK, dV=dV, workspace=ws,
-                      events=None if ev is None else (ev, base + 1))
+        if dropout is None:
+            spark_mha_fwd(Q, K, V, w.scale, w.causal, O=O, LSE=LSE)
+            spark_mha_bwd(Q, K, V, O, LSE, dO, w.scale, w.causal, dQ=dQ, dK=dK, dV=dV, workspace=ws,
+                          events=None if ev is None else (ev, base + 1))
+        else:
+            spark_mha_dropout_fwd(Q, K, V, w.scale, w.causal, *dropout, O=O, LSE=LSE)
+            if ev is not None:
+                ev.record(base + 1)
+            spark_mha_dropout_bwd(Q, K, V, O, LSE, dO, w.scale, w.causal, *dropout, dQ=dQ, dK=dK,
+                                  dV=dV, workspace=ws)
+            if ev is not None:
+                ev.record(base + 4)
 
     for _ in range(warmup):
         step()
@@ -76,10 +89,13 @@ def time_workload(w, steps, warmup):
         step(ev, 5 * s)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    k = {"fwd": 0.0, "bwd_dot": 0.0, "bwd_dkdv": 0.0, "bwd_dq": 0.0}
+    k = {"fwd": 0.0, "bwd": 0.0} if dropout else {"fwd": 0.0, "bwd_dot": 0.0, "bwd_dkdv": 0.0, "bwd_dq": 0.0}
     for s in range(steps):
         b = 5 * s
         k["fwd"] += ev.elapsed_ms(b, b + 1)
+        if dropout:
+            k["bwd"] += ev.elapsed_ms(b + 1, b + 4)
+            continue
         k["bwd_dot"] += ev.elapsed_ms(b + 1, b + 2)
         k["bwd_dkdv"] += ev.elapsed_ms(b + 2, b + 3)
         k["bwd_dq"] += ev.elapsed_ms(b + 3, b + 4)
@@ -196,10 +212,16 @@ def main():
                     ww = synth.Workload("S", 16384 // N, 2048 // d, N, d, synth.F16, causal, 1.0, 2000 + N + d)
                     m2, k2 = time_workload(ww, max(5, args.steps // 3), 2)
                     bwd_ms = k2["bwd_dot"] + k2["bwd_dkdv"] + k2["bwd_dq"]
+                    # the paper's measurements run with a dropout rate of 0.1 (Sec. 4.1)
+                    m3, k3 = time_workload(ww, max(5, args.steps // 3), 2, dropout=(0.1, 2024, 0))
                     sweep.append({"d": d, "N": N, "B": ww.B, "H": ww.H, "causal": causal,
                                   "fwd_tflops": ww.fwd_flops / (k2["fwd"] * 1e-3) / 1e12,
                                   "bwd_tflops": ww.bwd_flops / (bwd_ms * 1e-3) / 1e12,
-                                  "tflops": (ww.fwd_flops + ww.bwd_flops) / (m2 * 1e-3) / 1e12})
+                                  "tflops": (ww.fwd_flops + ww.bwd_flops) / (m2 * 1e-3) / 1e12,
+                                  "dropout_0.1": {
+                                      "fwd_tflops": ww.fwd_flops / (k3["fwd"] * 1e-3) / 1e12,
+                                      "bwd_tflops": ww.bwd_flops / (k3["bwd"] * 1e-3) / 1e12,
+                                      "tflops": (ww.fwd_flops + ww.bwd_flops) / (m3 * 1e-3) / 1e12}})
         out["paper_sweep"] = sweep
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w)

@@ -644,7 +644,6 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
   using v8 = typename F::v8;
   using C = BwdQCfg<D>;
   constexpr int KS = D / 16, DT = D / 32;
-  constexpr int NLD = C::BN * (D / 8) / 256;
 
   extern __shared__ __attribute__((aligned(16))) char smem_generic[];
   SPARK_LDS char* smem = (SPARK_LDS char*)smem_generic;
@@ -660,6 +659,13 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
   const size_t head_off = (size_t)head * Nq * D;    // Q, dO, dQ
   const size_t head_off_k = (size_t)head * Nk * D;  // K, V
   const BufView kview(K + head_off_k, (uint32_t)Nk * D * 2), vview(V + head_off_k, (uint32_t)Nk * D * 2);
+  const uint32_t lane_src = dma_lane_src<D>(wave, lane);
+  // K / V tiles go global -> LDS directly (no staging registers, no LDS store instructions);
+  // completion is awaited with wait_vmem_all + barrier at the end of the iteration before use.
+  auto fetch_tile = [&](int j, int buf) {
+    tile_dma<D, C::BN>(kview, j * C::BN, smem + buf * C::STAGE, wave, lane_src);
+    tile_dma<D, C::BN>(vview, j * C::BN, smem + buf * C::STAGE + C::TILE, wave, lane_src);
+  };
 
   for (int rep = 0; rep < (CAUSAL ? 2 : 1); ++rep) {
     const int qt = CAUSAL ? (rep == 0 ? nqt - 1 - item : item) : item;  // the long tile first
@@ -689,29 +695,22 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
 
     SwzLane<D> off(lane);  // read offsets of the current buffer; switched by one XOR each
 
-    u32x4 kreg[NLD], vreg[NLD];
     f32x16 dq[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) dq[dt][r] = 0.f;
 
-    tile_b2r<D, C::BN>(kview, 0, tid, kreg);
-    tile_b2r<D, C::BN>(vview, 0, tid, vreg);
+    fetch_tile(0, 0);
     wait_vmem_all();  // Q / dO fragments and the row statistics are in registers before the loop
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]), "+v"(dof[ks]));
     asm volatile("" : "+v"(lse2), "+v"(Dq));
-    tile_r2s_swz<D, C::BN>(smem, tid, kreg);
-    tile_r2s_swz<D, C::BN>(smem + C::TILE, tid, vreg);
     __syncthreads();
 
     for (int j = 0; j < nt; ++j) {
       const int buf = j & 1;
-      if (j + 1 < nt) {
-        tile_b2r<D, C::BN>(kview, (j + 1) * C::BN, tid, kreg);
-        tile_b2r<D, C::BN>(vview, (j + 1) * C::BN, tid, vreg);
-      }
+      if (j + 1 < nt) fetch_tile(j + 1, buf ^ 1);  // everybody left that buffer before the last barrier
       const int k0 = j * C::BN;
       if (!CAUSAL || k0 <= q0 + 31) {
         SPARK_LDS const char* kb = smem;  // + off.* (which carry the buffer bit)
@@ -795,16 +794,13 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
           sched_fence();
         }
       }
-      if (j + 1 < nt) {
-        tile_r2s_swz<D, C::BN>(smem + (buf ^ 1) * C::STAGE, tid, kreg);
-        tile_r2s_swz<D, C::BN>(smem + (buf ^ 1) * C::STAGE + C::TILE, tid, vreg);
-      }
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) off.row[ks] ^= C::STAGE;
 #pragma unroll
       for (int h = 0; h < 2; ++h)
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) off.tr[h][dt] ^= C::STAGE;
+      wait_vmem_all();  // the next tile has landed (requested at the top of the iteration)
       __syncthreads();
     }
 

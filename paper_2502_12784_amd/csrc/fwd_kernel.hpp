@@ -16,11 +16,11 @@
 //     of S^T are directly the B operand of that MFMA (see mma_gfx950.hpp), and the V^T
 //     operand comes from the row-major V tile in LDS through transposing LDS reads.  P never
 //     touches LDS or HBM (the paper's Sec. 3.2.2 layout transform becomes register renaming).
-//   * K/V tiles are double-buffered in LDS; the global loads of tile j+1 are issued before the
-//     arithmetic of tile j and written to the other buffer afterwards: one barrier per tile.
-//   * Row strides in LDS are padded (K: +16 B, V: +64 B) so the 16-byte row reads of K and
-//     the 4-row transposing reads of V spread over all banks (measured: conflict cycles are
-//     1.5 % of LDS-active cycles).
+//   * K/V tiles are double-buffered in LDS and arrive there by direct global->LDS loads (no
+//     staging registers, no LDS store instructions); tile j+1 is requested before the
+//     arithmetic of tile j and awaited before the one barrier that ends the iteration.
+//   * The tiles are unpadded and XOR-swizzled (tiles_gfx950.hpp) so that the 16-byte row reads
+//     of K and the 4-row transposing reads of V both spread over all banks.
 //   * Each 64-key tile runs as two 32-key online-softmax steps whose VALU work is interleaved,
 //     in program order, with the MFMAs of the other half (a wave issues in order); LDS operand
 //     reads are issued several MFMAs ahead and pinned there with scheduler fences.
@@ -37,14 +37,13 @@ namespace spark {
 template <int D> struct FwdCfg {
   static constexpr int BM = 128;  // query rows per workgroup (32 per wave)
   static constexpr int BN = 64;   // keys per iteration
-  static constexpr int KSTR = D * 2 + 16;
-  static constexpr int VSTR = D * 2 + 64;
-  static constexpr int KBYTES = BN * KSTR;
-  static constexpr int VBYTES = BN * VSTR;
-  static constexpr int STAGE = KBYTES + VBYTES;
+  static constexpr int ROWB = D * 2;      // bytes per (swizzled, unpadded) row
+  static constexpr int TILE = BN * ROWB;  // one of K, V
+  static constexpr int STAGE = 2 * TILE;  // power of two: the buffer is switched by one XOR
   static constexpr int OSTR = D * 2 + 16;  // epilogue staging row stride
   static constexpr int SMEM = 2 * STAGE;
   static_assert(4 * 32 * OSTR <= SMEM, "epilogue staging must fit in the K/V buffers");
+  static_assert((STAGE & (STAGE - 1)) == 0, "XOR buffer switch");
 };
 
 template <typename T, int D, bool CAUSAL, bool DROP>
@@ -59,13 +58,13 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
   constexpr int KS = D / 16;   // k-steps of the score contraction
   constexpr int DT = D / 32;   // 32-row tiles of O^T
   constexpr int CPR = D / 8;   // 16-byte chunks per row
-  constexpr int NLD = C::BN * CPR / 256;  // chunks per thread per tile
 
   extern __shared__ __attribute__((aligned(16))) char smem_generic[];
   SPARK_LDS char* smem = (SPARK_LDS char*)smem_generic;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int g = lane >> 5, c32 = lane & 31, i16 = lane & 15;
+  const int g = lane >> 5, c32 = lane & 31;
+  const uint32_t lane_src = dma_lane_src<D>(wave, lane);
 
   // Work items.  Non-causal: one query tile per workgroup.  Causal: a workgroup takes the pair
   // of tiles (nqt-1-p, p), whose loop lengths add up to the same total for every p, so that
@@ -105,26 +104,13 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
     }
     const int nt = (kv_end + C::BN - 1) / C::BN;
 
-    // Tile loads: thread t owns 16-byte chunk t of each group of 256 chunks (= 4096 bytes).
+    // K / V tiles: global -> LDS directly; rows past the end of the sequence arrive as zeros.
     const BufView kview(Kh, (uint32_t)Nk * D * 2), vview(Vh, (uint32_t)Nk * D * 2);
-    u32x4 kreg[NLD], vreg[NLD];
-    auto load_tile = [&](int j) {
-      const uint32_t tile_off = (uint32_t)j * (C::BN * D * 2);
-#pragma unroll
-      for (int i = 0; i < NLD; ++i) {
-        kreg[i] = kview.load16(tid * 16 + i * 4096, tile_off);
-        vreg[i] = vview.load16(tid * 16 + i * 4096, tile_off);
-      }
+    auto fetch_tile = [&](int j, int buf) {
+      tile_dma<D, C::BN>(kview, j * C::BN, smem + buf * C::STAGE, wave, lane_src);
+      tile_dma<D, C::BN>(vview, j * C::BN, smem + buf * C::STAGE + C::TILE, wave, lane_src);
     };
-    auto store_tile = [&](int buf) {
-#pragma unroll
-      for (int i = 0; i < NLD; ++i) {
-        const int c = tid + 256 * i;
-        const int row = c / CPR, cc = c % CPR;
-        lds_write(smem, buf * C::STAGE + row * C::KSTR + cc * 16, kreg[i]);
-        lds_write(smem, buf * C::STAGE + C::KBYTES + row * C::VSTR + cc * 16, vreg[i]);
-      }
-    };
+    SwzLane<D> off(lane);  // read offsets of the current buffer; switched by one XOR each
 
     f32x16 o[DT];
 #pragma unroll
@@ -134,23 +120,22 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
     float m_run = -INFINITY;  // running row max (log2 domain)
     float l_run = 0.f;        // running row sum over this lane's keys only (halves merged at the end)
 
-    load_tile(0);
+    fetch_tile(0, 0);
     // The Q fragments must have arrived before the loop: otherwise the waits for them would sit
-    // inside the loop body and would also wait for the next tile's prefetch every iteration.
+    // inside the loop body.
     wait_vmem_all();
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]));
-    store_tile(0);
     __syncthreads();
 
     for (int j = 0; j < nt; ++j) {
       const int buf = j & 1;
-      if (j + 1 < nt) load_tile(j + 1);
+      if (j + 1 < nt) fetch_tile(j + 1, buf ^ 1);  // everybody left that buffer before the last barrier
 
       const int k0 = j * C::BN;
       if (!CAUSAL || k0 <= q0 + 31) {  // wave-uniform: skip tiles entirely above the diagonal
-        SPARK_LDS const char* kb = smem + buf * C::STAGE;
-        SPARK_LDS const char* vb = kb + C::KBYTES;
+        SPARK_LDS const char* kb = smem;  // + off.* (which carry the buffer bit)
+        SPARK_LDS const char* vb = smem + C::TILE;
 
         // The 64-key tile is processed as two 32-key halves, each its own online-softmax step,
         // so that the VALU work of one half sits between the MFMAs of the other:
@@ -172,18 +157,14 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
           const int half = gi / GPH, ks0 = 4 * (gi % GPH);
 #pragma unroll
           for (int e = 0; e < 4; ++e)
-            kf[gi & 1][e] = lds_read16<v8>(kb, (half * 32 + c32) * C::KSTR + (ks0 + e) * 32 + g * 16);
+            kf[gi & 1][e] = lds_read16<v8>(kb, off.row[ks0 + e] + half * 32 * C::ROWB);
         };
         v8 vf[2][DT];
         auto load_vgroup = [&](int kk) {
-          const int row0 = 16 * kk + 4 * g + (i16 >> 2);
+          const int o = kk * 16 * C::ROWB;
 #pragma unroll
-          for (int dt = 0; dt < DT; ++dt) {
-            const int col = dt * 32 + (c32 & 16) + 4 * (i16 & 3);
-            const v4 lo = lds_read_tr8<v4>(vb, row0 * C::VSTR + col * 2);
-            const v4 hi = lds_read_tr8<v4>(vb, (row0 + 8) * C::VSTR + col * 2);
-            vf[kk & 1][dt] = join4<v8, v4>(lo, hi);
-          }
+          for (int dt = 0; dt < DT; ++dt)
+            vf[kk & 1][dt] = read_tr_pair<T>(vb, off.tr[0][dt] + o, off.tr[1][dt] + o);
         };
 
         const bool need_mask = (CAUSAL && k0 + C::BN - 1 > q0) || (k0 + C::BN > Nk);
@@ -317,7 +298,13 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
         }
       }
 
-      if (j + 1 < nt) store_tile(buf ^ 1);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) off.row[ks] ^= C::STAGE;
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) off.tr[h][dt] ^= C::STAGE;
+      wait_vmem_all();  // the next tile has landed (requested at the top of the iteration)
       __syncthreads();
     }
 
