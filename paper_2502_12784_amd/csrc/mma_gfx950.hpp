@@ -105,18 +105,13 @@ static __device__ __forceinline__ float half_pair_sum(float x) {
 // and the per-tile part of the address is a scalar offset (no vector address arithmetic in the
 // main loops).  The matrix must be smaller than 4 GiB.
 struct BufView {
-  __amdgpu_buffer_rsrc_t rsrc;
-  u32x4 desc;  // the same descriptor as four dwords (base, base_hi | stride 0, bytes, flags)
-  __device__ __forceinline__ BufView(const void* base, uint32_t bytes)
-      : rsrc(__builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000)) {
+  u32x4 desc;  // buffer descriptor: base, base_hi | stride 0, bytes, flags
+  __device__ __forceinline__ BufView(const void* base, uint32_t bytes) {
     const uint64_t a = reinterpret_cast<uint64_t>(base);
     desc[0] = (uint32_t)a;
     desc[1] = (uint32_t)(a >> 32) & 0xffffu;
     desc[2] = bytes;
     desc[3] = 0x00020000u;
-  }
-  __device__ __forceinline__ u32x4 load16(uint32_t lane_off, uint32_t tile_off) const {
-    return __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane_off, tile_off, 0);
   }
   // Direct global->LDS load (no registers): lane l of the wave writes its 16 (or 4) bytes at
   // LDS byte address dst + 16 l (4 l); dst must be wave-uniform.  Out-of-range lanes write

@@ -96,7 +96,7 @@ int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const
                        LSE2ws, rows, DROP ? dr.keep_prob : 1.0f);
     if (hipGetLastError() != hipSuccess || !mark(1)) return SPARK_ERR_LAUNCH;
   }
-  if constexpr (D == 128) {  // dK, dV: one workgroup per tile of 128 keys, software-pipelined
+  {  // dK, dV: one workgroup per tile of 128 keys, software-pipelined
     using C = BwdKvPipeCfg<D>;
     auto kernel = mha_bwd_dkdv_pipe_kernel<T, D, CAUSAL, DROP>;
     static const int attr = set_smem(kernel, C::SMEM);
@@ -104,16 +104,6 @@ int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const
     const int nkt = (Nk + C::BN - 1) / C::BN;
     hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nkt))), dim3(256), C::SMEM, st, q, k, v, dout,
                        LSE2ws, Dws, static_cast<T*>(dK), static_cast<T*>(dV), Nq, Nk, nkt, scale, dr);
-    if (hipGetLastError() != hipSuccess || !mark(2)) return SPARK_ERR_LAUNCH;
-  } else {  // dK, dV: one workgroup per tile of 128 keys, two workgroups per CU
-    using C = BwdKvCfg<D>;
-    auto kernel = mha_bwd_dkdv_kernel<T, D, CAUSAL, DROP>;
-    static const int attr = set_smem(kernel, C::SMEM);
-    if (attr != SPARK_OK) return attr;
-    const int nkt = (Nk + C::BN - 1) / C::BN;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nkt))), dim3(256), C::SMEM, st, q, k, v, dout,
-                       LSE, Dws, static_cast<T*>(dK), static_cast<T*>(dV), Nq, Nk, nkt, scale,
-                       scale_log2, dr);
     if (hipGetLastError() != hipSuccess || !mark(2)) return SPARK_ERR_LAUNCH;
   }
   {  // dQ: one workgroup per tile of 128 queries

@@ -45,27 +45,6 @@ static __device__ __forceinline__ int swz_off(int row, int chunk) {
   return row * (2 * D) + ((chunk ^ swz<D>(row)) << 4);
 }
 
-// registers -> swizzled tile (thread t owns chunk t of every group of 256 chunks)
-template <int D, int ROWS>
-static __device__ __forceinline__ void tile_r2s_swz(SPARK_LDS char* dst, int tid,
-                                                    const u32x4 (&reg)[ROWS * (D / 8) / 256]) {
-  constexpr int CPR = D / 8;
-#pragma unroll
-  for (int i = 0; i < ROWS * CPR / 256; ++i) {
-    const int c = tid + 256 * i;
-    lds_write(dst, swz_off<D>(c / CPR, c % CPR), reg[i]);
-  }
-}
-
-// global (buffer view) -> registers, rows r0.. of a [N][D] matrix; rows past N read as zero
-template <int D, int ROWS>
-static __device__ __forceinline__ void tile_b2r(const BufView& view, int r0, int tid,
-                                                u32x4 (&reg)[ROWS * (D / 8) / 256]) {
-#pragma unroll
-  for (int i = 0; i < ROWS * (D / 8) / 256; ++i)
-    reg[i] = view.load16(tid * 16 + i * 4096, (uint32_t)r0 * (D * 2));
-}
-
 // Per-lane byte offsets into a swizzled tile.
 //   row[ks]   : 16-byte row read, row c32, logical chunk 2*ks + g      (A/B operand over d)
 //   tr[h][dt] : transposing read for d-tile dt, rows 8h + 4g + i16/4   (operand over rows)
