@@ -24,7 +24,7 @@
  *     alias each other.
  *   - Supported: d in {64, 128}; any N >= 1; B, H >= 1; scale finite and > 0; causal is
  *     a flag (0 = all keys, nonzero = masked).  Size limits: B*H*ceil(N/64) < 2^31 and
- *     N*d < 2^31.  Anything else returns SPARK_ERR_SHAPE; nothing is silently mis-computed.
+ *     (N + 256)*d < 2^31.  Anything else returns SPARK_ERR_SHAPE; nothing is silently mis-computed.
  *   - causal != 0: query i attends to keys j <= i (Sec. 2.1, masked MHA).
  *   - The spark_mha_cross_* entry points take Nq query rows and Nk key/value rows (Sec. 2.1:
  *     the decoder's second attention layer attends to the encoder output, so S of Eq. 1 is
@@ -58,9 +58,10 @@ typedef enum {
   SPARK_OK = 0,
   SPARK_ERR_NULL = -1,      /* a required pointer is NULL */
   SPARK_ERR_SHAPE = -2,     /* B, H or N < 1; d not 64/128; a size limit exceeded; scale not
-                               finite or <= 0; causal with Nq != Nk; invalid p_drop */
+                               finite or <= 0; causal with Nq != Nk; invalid p_drop; row stride < d or
+                               a head spanning 4 GiB or more */
   SPARK_ERR_DTYPE = -3,     /* dtype is neither SPARK_F16 nor SPARK_BF16 */
-  SPARK_ERR_ALIGN = -4,     /* a pointer is not 16-byte aligned */
+  SPARK_ERR_ALIGN = -4,     /* a pointer, or a stride in bytes, is not a multiple of 16 */
   SPARK_ERR_WORKSPACE = -5, /* workspace too small (see spark_mha_bwd_workspace_bytes) */
   SPARK_ERR_LAUNCH = -6     /* the HIP runtime refused a launch */
 } spark_status_t;
@@ -183,6 +184,39 @@ int spark_dropout_threshold(float p_drop);
  */
 int spark_dropout_mask(unsigned char* M, int B, int H, int Nq, int Nk, float p_drop,
                        unsigned long long seed, unsigned offset, void* stream);
+
+/*
+ * Strided tensors: the most general forms.  Every [B,H,N,d] tensor gets its own element strides
+ * for the batch, head and row (sequence) indices; the d elements of a row stay contiguous.  A
+ * projection output laid out [B,N,H,d] is {N*H*d, d, H*d}; the contiguous default of the other
+ * entry points is {H*N*d, N*d, d}.  Requirements per tensor: row >= d; batch, head >= 0; all
+ * three multiples of 8 elements (16 bytes), else SPARK_ERR_ALIGN; (N + 256) * row * 2 < 2^32 bytes
+ * (one head is addressed with 32-bit offsets), else SPARK_ERR_SHAPE; a NULL strides pointer is SPARK_ERR_NULL.  Output tensors must
+ * not overlap themselves or anything else (not checked).  LSE and the workspace are always
+ * contiguous [B,H,Nq].  Cross-attention (Nq, Nk) and dropout (p_drop, seed, offset; p_drop = 0
+ * for none) as in the entry points above; same kernels, same guarantees.
+ */
+typedef struct {
+  long long batch, head, row; /* element strides; d is contiguous */
+} spark_strides_t;
+
+int spark_mha_strided_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                          const spark_strides_t* sQ, const spark_strides_t* sK,
+                          const spark_strides_t* sV, const spark_strides_t* sO,
+                          int B, int H, int Nq, int Nk, int d, float scale, int causal,
+                          float p_drop, unsigned long long seed, unsigned offset,
+                          spark_dtype_t dtype, void* stream);
+
+int spark_mha_strided_bwd(const void* Q, const void* K, const void* V, const void* O,
+                          const float* LSE, const void* dO, void* dQ, void* dK, void* dV,
+                          const spark_strides_t* sQ, const spark_strides_t* sK,
+                          const spark_strides_t* sV, const spark_strides_t* sO,
+                          const spark_strides_t* sdO, const spark_strides_t* sdQ,
+                          const spark_strides_t* sdK, const spark_strides_t* sdV,
+                          void* workspace, size_t workspace_bytes,
+                          int B, int H, int Nq, int Nk, int d, float scale, int causal,
+                          float p_drop, unsigned long long seed, unsigned offset,
+                          spark_dtype_t dtype, void* stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char* spark_status_str(int status);

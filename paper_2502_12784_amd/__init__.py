@@ -7,6 +7,7 @@ from .binding import (  # noqa: F401
     EXPORTS,
     HipEvents,
     SparkError,
+    Strides,
     load_library,
     spark_dropout_mask,
     spark_dropout_threshold,
@@ -18,5 +19,7 @@ from .binding import (  # noqa: F401
     spark_mha_dropout_bwd,
     spark_mha_dropout_fwd,
     spark_mha_fwd,
+    spark_mha_strided_bwd,
+    spark_mha_strided_fwd,
     status_str,
 )

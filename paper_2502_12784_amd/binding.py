@@ -19,9 +19,15 @@ SPARK_BF16 = 1
 EXPORTS = ("spark_mha_fwd", "spark_mha_bwd", "spark_mha_bwd_marked",
            "spark_mha_bwd_workspace_bytes", "spark_mha_cross_fwd", "spark_mha_cross_bwd",
            "spark_mha_cross_bwd_workspace_bytes", "spark_mha_dropout_fwd", "spark_mha_dropout_bwd",
-           "spark_dropout_threshold", "spark_dropout_mask", "spark_status_str")
+           "spark_dropout_threshold", "spark_dropout_mask", "spark_mha_strided_fwd",
+           "spark_mha_strided_bwd", "spark_status_str")
 
 _lib = None
+
+
+class Strides(ctypes.Structure):
+    """spark_strides_t: element strides of the batch, head and row indices."""
+    _fields_ = [("batch", ctypes.c_longlong), ("head", ctypes.c_longlong), ("row", ctypes.c_longlong)]
 
 
 class SparkError(RuntimeError):
@@ -62,6 +68,12 @@ def load_library() -> ctypes.CDLL:
     lib.spark_dropout_threshold.argtypes = [f]
     lib.spark_dropout_mask.restype = i
     lib.spark_dropout_mask.argtypes = [vp, i, i, i, i, f, u64, u32, vp]
+    sp = ctypes.POINTER(Strides)
+    lib.spark_mha_strided_fwd.restype = i
+    lib.spark_mha_strided_fwd.argtypes = [vp] * 5 + [sp] * 4 + [i, i, i, i, i, f, i, f, u64, u32, i, vp]
+    lib.spark_mha_strided_bwd.restype = i
+    lib.spark_mha_strided_bwd.argtypes = ([vp] * 9 + [sp] * 8 + [vp, ctypes.c_size_t, i, i, i, i, i, f, i,
+                                                             f, u64, u32, i, vp])
     lib.spark_mha_bwd_marked.restype = i
     lib.spark_mha_bwd_marked.argtypes = lib.spark_mha_bwd.argtypes + [ctypes.POINTER(vp)]
     lib.spark_status_str.restype = ctypes.c_char_p
@@ -216,6 +228,67 @@ def spark_mha_cross_bwd(Q, K, V, O, LSE, dO, scale: float, causal: bool = False,
         p_drop, seed, offset = dropout
         _check(lib.spark_mha_dropout_bwd(*ptrs, B, H, Nq, Nk, d, float(scale), int(bool(causal)),
                                          float(p_drop), int(seed), int(offset), code, _stream_ptr()))
+    return dQ, dK, dV
+
+
+def _strided(t, shape, dtype, name):
+    """Check a [B,H,N,d] view whose last dimension is contiguous; return its spark_strides_t."""
+    if not t.is_cuda:
+        raise ValueError("%s must be a device tensor" % name)
+    if tuple(t.shape) != tuple(shape) or t.dtype != dtype or t.stride(3) != 1:
+        raise ValueError("%s must be a %s view of shape %s with contiguous last dimension"
+                         % (name, dtype, tuple(shape)))
+    return Strides(t.stride(0), t.stride(1), t.stride(2))
+
+
+def spark_mha_strided_fwd(Q, K, V, scale: float, causal: bool = False, p_drop: float = 0.0,
+                          seed: int = 0, offset: int = 0, O=None, LSE=None):
+    """Forward on [B,H,N,d] views with arbitrary batch/head/row strides (e.g. a permuted
+    [B,N,H,d] projection output, or slices of a packed QKV buffer)."""
+    import torch
+    lib = load_library()
+    B, H, Nq, d = Q.shape
+    Nk = K.shape[2]
+    if O is None:
+        O = torch.empty_like(Q)  # keeps Q's (dense) layout
+    if LSE is None:
+        LSE = torch.empty((B, H, Nq), dtype=torch.float32, device=Q.device)
+    sq, so = _strided(Q, (B, H, Nq, d), Q.dtype, "Q"), _strided(O, (B, H, Nq, d), Q.dtype, "O")
+    sk, sv = _strided(K, (B, H, Nk, d), Q.dtype, "K"), _strided(V, (B, H, Nk, d), Q.dtype, "V")
+    _require(LSE, (B, H, Nq), torch.float32, "LSE")
+    _check(lib.spark_mha_strided_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                                     LSE.data_ptr(), sq, sk, sv, so, B, H, Nq, Nk, d, float(scale),
+                                     int(bool(causal)), float(p_drop), int(seed), int(offset),
+                                     _dtype_code(Q), _stream_ptr()))
+    return O, LSE
+
+
+def spark_mha_strided_bwd(Q, K, V, O, LSE, dO, scale: float, causal: bool = False,
+                          p_drop: float = 0.0, seed: int = 0, offset: int = 0, dQ=None, dK=None,
+                          dV=None, workspace=None):
+    """Backward on strided [B,H,N,d] views; gradients default to the layouts of Q, K, V."""
+    import torch
+    lib = load_library()
+    B, H, Nq, d = Q.shape
+    Nk = K.shape[2]
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    qs, ks = (B, H, Nq, d), (B, H, Nk, d)
+    st = [_strided(Q, qs, Q.dtype, "Q"), _strided(K, ks, Q.dtype, "K"), _strided(V, ks, Q.dtype, "V"),
+          _strided(O, qs, Q.dtype, "O"), _strided(dO, qs, Q.dtype, "dO"), _strided(dQ, qs, Q.dtype, "dQ"),
+          _strided(dK, ks, Q.dtype, "dK"), _strided(dV, ks, Q.dtype, "dV")]
+    _require(LSE, (B, H, Nq), torch.float32, "LSE")
+    code = _dtype_code(Q)
+    need = spark_mha_cross_bwd_workspace_bytes(B, H, Nq, Nk, d, code)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
+    wbytes = workspace.numel() * workspace.element_size()
+    _check(lib.spark_mha_strided_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                                     LSE.data_ptr(), dO.data_ptr(), dQ.data_ptr(), dK.data_ptr(),
+                                     dV.data_ptr(), *st, workspace.data_ptr(), wbytes, B, H, Nq, Nk, d,
+                                     float(scale), int(bool(causal)), float(p_drop), int(seed),
+                                     int(offset), code, _stream_ptr()))
     return dQ, dK, dV
 
 

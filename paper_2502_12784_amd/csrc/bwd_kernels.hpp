@@ -39,16 +39,18 @@ __global__ __launch_bounds__(256) void mha_bwd_dot_kernel(const T* __restrict__ 
                                                          const T* __restrict__ dO,
                                                          const float* __restrict__ LSE,
                                                          float* __restrict__ Dout,
-                                                         float* __restrict__ LSE2out, int64_t rows,
+                                                         float* __restrict__ LSE2out, TensorMap mo,
+                                                         TensorMap mdo, int H, int Nq, int64_t rows,
                                                          float dscale) {
   using v8 = typename Frag<T>::v8;
   constexpr int CPR = D / 8;
   const int64_t chunk = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t row = chunk / CPR;
+  const int64_t row = chunk / CPR;  // flat (batch, head, query) index
   float acc = 0.f;
   if (row < rows) {
-    const v8 a = *reinterpret_cast<const v8*>(O + chunk * 8);
-    const v8 b = *reinterpret_cast<const v8*>(dO + chunk * 8);
+    const int bh = (int)(row / Nq), n = (int)(row - (int64_t)bh * Nq), c = (int)(chunk - row * CPR);
+    const v8 a = *reinterpret_cast<const v8*>(O + head_base(mo, bh, H) + (size_t)n * (size_t)mo.row + c * 8);
+    const v8 b = *reinterpret_cast<const v8*>(dO + head_base(mdo, bh, H) + (size_t)n * (size_t)mdo.row + c * 8);
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc += (float)a[i] * (float)b[i];
   }
@@ -94,7 +96,8 @@ template <typename T, int D, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_pipe_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ dO, const float* __restrict__ LSE2, const float* __restrict__ Dws,
-    T* __restrict__ dK, T* __restrict__ dV, int Nq, int Nk, int nkt, float scale, Dropout dr) {
+    T* __restrict__ dK, T* __restrict__ dV, TensorMap mq, TensorMap mk, TensorMap mv, TensorMap mdo,
+    TensorMap mdk, TensorMap mdv, int H, int Nq, int Nk, int nkt, float scale, Dropout dr) {
   using F = Frag<T>;
   using v8 = typename F::v8;
   using C = BwdKvPipeCfg<D>;
@@ -111,11 +114,14 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_pipe_kernel
   const int head = logical / items;
   const int item = logical - head * items;
 
-  const size_t head_off = (size_t)head * Nq * D;    // Q, dO
-  const size_t head_off_k = (size_t)head * Nk * D;  // K, V, dK, dV
-  const BufView qview(Q + head_off, (uint32_t)Nq * D * 2), doview(dO + head_off, (uint32_t)Nq * D * 2);
+  const T* Kh = K + head_base(mk, head, H);
+  const T* Vh = V + head_base(mv, head, H);
+  const BufView qview(Q + head_base(mq, head, H), head_span_bytes<D>(mq, Nq));
+  const BufView doview(dO + head_base(mdo, head, H), head_span_bytes<D>(mdo, Nq));
+  const uint32_t q_row_bytes = (uint32_t)mq.row * 2, do_row_bytes = (uint32_t)mdo.row * 2;
   const BufView lview(LSE2 + (size_t)head * Nq, (uint32_t)Nq * 4), dview(Dws + (size_t)head * Nq, (uint32_t)Nq * 4);
-  const uint32_t lane_src = dma_lane_src<D>(wave, lane);
+  const uint32_t q_lane_src = dma_lane_src<D>(wave, lane, q_row_bytes);
+  const uint32_t do_lane_src = dma_lane_src<D>(wave, lane, do_row_bytes);
   const float scale_log2 = scale * 1.4426950408889634f;
 
   for (int rep = 0; rep < (CAUSAL ? 2 : 1); ++rep) {
@@ -131,8 +137,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_pipe_kernel
     v8 kf[KS], vf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      kf[ks] = *reinterpret_cast<const v8*>(K + head_off_k + (size_t)krow_c * D + ks * 16 + g * 8);
-      vf[ks] = *reinterpret_cast<const v8*>(V + head_off_k + (size_t)krow_c * D + ks * 16 + g * 8);
+      kf[ks] = *reinterpret_cast<const v8*>(Kh + (size_t)krow_c * (size_t)mk.row + ks * 16 + g * 8);
+      vf[ks] = *reinterpret_cast<const v8*>(Vh + (size_t)krow_c * (size_t)mv.row + ks * 16 + g * 8);
     }
 
     f32x16 dk[DT], dv[DT];
@@ -150,8 +156,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_pipe_kernel
     // global -> LDS slot, asynchronously (completion is awaited with wait_vmem_all + barrier)
     auto fetch_stage = [&](int m, int slot) {
       SPARK_LDS char* sb = smem + slot * C::STAGE;
-      tile_dma<D, C::BM>(qview, m * C::BM, sb, wave, lane_src);
-      tile_dma<D, C::BM>(doview, m * C::BM, sb + C::TILE, wave, lane_src);
+      tile_dma<D, C::BM>(qview, m * C::BM, sb, wave, q_lane_src, q_row_bytes);
+      tile_dma<D, C::BM>(doview, m * C::BM, sb + C::TILE, wave, do_lane_src, do_row_bytes);
       // 64 floats of LSE*log2(e) (wave 0) and of D (wave 1): 4 bytes per lane
       SPARK_LDS char* st = smem + C::STAT0 + slot * C::STAT;
       if (wave == 0) lview.load4_to_lds(st, lane * 4, (uint32_t)m * C::BM * 4);
@@ -374,8 +380,10 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_pipe_kernel
     }
 
     SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
-    store_transposed<T, D, C::OSTR>(dk, DROP ? scale * dr.rescale : scale, ob, dK + head_off_k, k0w, Nk, lane);
-    store_transposed<T, D, C::OSTR>(dv, DROP ? dr.rescale : 1.0f, ob, dV + head_off_k, k0w, Nk, lane);
+    store_transposed<T, D, C::OSTR>(dk, DROP ? scale * dr.rescale : scale, ob, dK + head_base(mdk, head, H), k0w,
+                                    Nk, lane, (size_t)mdk.row);
+    store_transposed<T, D, C::OSTR>(dv, DROP ? dr.rescale : 1.0f, ob, dV + head_base(mdv, head, H), k0w, Nk,
+                                    lane, (size_t)mdv.row);
   }  // rep
 }
 
@@ -399,7 +407,8 @@ template <typename T, int D, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Dws,
-    T* __restrict__ dQ, int Nq, int Nk, int nqt, float scale, float scale_log2, Dropout dr) {
+    T* __restrict__ dQ, TensorMap mq, TensorMap mk, TensorMap mv, TensorMap mdo, TensorMap mdq, int H,
+    int Nq, int Nk, int nqt, float scale, float scale_log2, Dropout dr) {
   using F = Frag<T>;
   using v8 = typename F::v8;
   using C = BwdQCfg<D>;
@@ -416,15 +425,18 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
   const int head = logical / items;
   const int item = logical - head * items;
 
-  const size_t head_off = (size_t)head * Nq * D;    // Q, dO, dQ
-  const size_t head_off_k = (size_t)head * Nk * D;  // K, V
-  const BufView kview(K + head_off_k, (uint32_t)Nk * D * 2), vview(V + head_off_k, (uint32_t)Nk * D * 2);
-  const uint32_t lane_src = dma_lane_src<D>(wave, lane);
+  const T* Qh = Q + head_base(mq, head, H);
+  const T* dOh = dO + head_base(mdo, head, H);
+  const BufView kview(K + head_base(mk, head, H), head_span_bytes<D>(mk, Nk));
+  const BufView vview(V + head_base(mv, head, H), head_span_bytes<D>(mv, Nk));
+  const uint32_t k_row_bytes = (uint32_t)mk.row * 2, v_row_bytes = (uint32_t)mv.row * 2;
+  const uint32_t k_lane_src = dma_lane_src<D>(wave, lane, k_row_bytes);
+  const uint32_t v_lane_src = dma_lane_src<D>(wave, lane, v_row_bytes);
   // K / V tiles go global -> LDS directly (no staging registers, no LDS store instructions);
   // completion is awaited with wait_vmem_all + barrier at the end of the iteration before use.
   auto fetch_tile = [&](int j, int buf) {
-    tile_dma<D, C::BN>(kview, j * C::BN, smem + buf * C::STAGE, wave, lane_src);
-    tile_dma<D, C::BN>(vview, j * C::BN, smem + buf * C::STAGE + C::TILE, wave, lane_src);
+    tile_dma<D, C::BN>(kview, j * C::BN, smem + buf * C::STAGE, wave, k_lane_src, k_row_bytes);
+    tile_dma<D, C::BN>(vview, j * C::BN, smem + buf * C::STAGE + C::TILE, wave, v_lane_src, v_row_bytes);
   };
 
   for (int rep = 0; rep < (CAUSAL ? 2 : 1); ++rep) {
@@ -440,8 +452,8 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
     v8 qf[KS], dof[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      qf[ks] = *reinterpret_cast<const v8*>(Q + head_off + (size_t)qrow_c * D + ks * 16 + g * 8);
-      dof[ks] = *reinterpret_cast<const v8*>(dO + head_off + (size_t)qrow_c * D + ks * 16 + g * 8);
+      qf[ks] = *reinterpret_cast<const v8*>(Qh + (size_t)qrow_c * (size_t)mq.row + ks * 16 + g * 8);
+      dof[ks] = *reinterpret_cast<const v8*>(dOh + (size_t)qrow_c * (size_t)mdo.row + ks * 16 + g * 8);
     }
     float lse2 = LSE[(size_t)head * Nq + qrow_c] * 1.4426950408889634f;
     float Dq = Dws[(size_t)head * Nq + qrow_c];
@@ -565,7 +577,8 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
     }
 
     SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
-    store_transposed<T, D, C::OSTR>(dq, DROP ? scale * dr.rescale : scale, ob, dQ + head_off, q0, Nq, lane);
+    store_transposed<T, D, C::OSTR>(dq, DROP ? scale * dr.rescale : scale, ob, dQ + head_base(mdq, head, H), q0,
+                                    Nq, lane, (size_t)mdq.row);
   }  // rep
 }
 

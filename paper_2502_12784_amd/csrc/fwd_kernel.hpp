@@ -49,8 +49,8 @@ template <int D> struct FwdCfg {
 template <typename T, int D, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
-    T* __restrict__ O, float* __restrict__ LSE, int Nq, int Nk, int nqt, float scale_log2,
-    Dropout dr) {
+    T* __restrict__ O, float* __restrict__ LSE, TensorMap mq, TensorMap mk, TensorMap mv,
+    TensorMap mo, int H, int Nq, int Nk, int nqt, float scale_log2, Dropout dr) {
   using F = Frag<T>;
   using v8 = typename F::v8;
   using v4 = typename F::v4;
@@ -64,7 +64,9 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, c32 = lane & 31;
-  const uint32_t lane_src = dma_lane_src<D>(wave, lane);
+  const uint32_t k_row_bytes = (uint32_t)mk.row * 2, v_row_bytes = (uint32_t)mv.row * 2;
+  const uint32_t k_lane_src = dma_lane_src<D>(wave, lane, k_row_bytes);
+  const uint32_t v_lane_src = dma_lane_src<D>(wave, lane, v_row_bytes);
 
   // Work items.  Non-causal: one query tile per workgroup.  Causal: a workgroup takes the pair
   // of tiles (nqt-1-p, p), whose loop lengths add up to the same total for every p, so that
@@ -75,11 +77,9 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
   const int item = logical - head * items;
 
   // Nq query rows and Nk key rows per head (equal for self-attention; causal needs them equal)
-  const size_t head_off = (size_t)head * Nq * D;
-  const size_t head_off_k = (size_t)head * Nk * D;
-  const T* Qh = Q + head_off;
-  const T* Kh = K + head_off_k;
-  const T* Vh = V + head_off_k;
+  const T* Qh = Q + head_base(mq, head, H);
+  const T* Kh = K + head_base(mk, head, H);
+  const T* Vh = V + head_base(mv, head, H);
 
   for (int rep = 0; rep < (CAUSAL ? 2 : 1); ++rep) {
     const int qt = CAUSAL ? (rep == 0 ? nqt - 1 - item : item) : item;
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
     v8 qf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
-      qf[ks] = *reinterpret_cast<const v8*>(Qh + (size_t)qrow_c * D + ks * 16 + g * 8);
+      qf[ks] = *reinterpret_cast<const v8*>(Qh + (size_t)qrow_c * (size_t)mq.row + ks * 16 + g * 8);
 
     int kv_end = Nk;
     if (CAUSAL) {
@@ -105,10 +105,10 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
     const int nt = (kv_end + C::BN - 1) / C::BN;
 
     // K / V tiles: global -> LDS directly; rows past the end of the sequence arrive as zeros.
-    const BufView kview(Kh, (uint32_t)Nk * D * 2), vview(Vh, (uint32_t)Nk * D * 2);
+    const BufView kview(Kh, head_span_bytes<D>(mk, Nk)), vview(Vh, head_span_bytes<D>(mv, Nk));
     auto fetch_tile = [&](int j, int buf) {
-      tile_dma<D, C::BN>(kview, j * C::BN, smem + buf * C::STAGE, wave, lane_src);
-      tile_dma<D, C::BN>(vview, j * C::BN, smem + buf * C::STAGE + C::TILE, wave, lane_src);
+      tile_dma<D, C::BN>(kview, j * C::BN, smem + buf * C::STAGE, wave, k_lane_src, k_row_bytes);
+      tile_dma<D, C::BN>(vview, j * C::BN, smem + buf * C::STAGE + C::TILE, wave, v_lane_src, v_row_bytes);
     };
     SwzLane<D> off(lane);  // read offsets of the current buffer; switched by one XOR each
 
@@ -321,13 +321,13 @@ __global__ __launch_bounds__(256, 2) void mha_fwd_kernel(
         for (int e = 0; e < 4; ++e) pk[e] = (T)(o[dt][r4 * 4 + e] * inv);
         lds_write(ob, c32 * C::OSTR + (dt * 32 + 8 * r4 + 4 * g) * 2, pk);
       }
-    T* Oh = O + head_off;
+    T* Oh = O + head_base(mo, head, H);
     constexpr int RPP = 64 / CPR;  // rows per pass of the wave
 #pragma unroll
     for (int p = 0; p < 32 / RPP; ++p) {
       const int row = p * RPP + lane / CPR, cc = lane % CPR;
       const u32x4 v = lds_read16<u32x4>(ob, row * C::OSTR + cc * 16);
-      if (q0 + row < Nq) *reinterpret_cast<u32x4*>(Oh + (size_t)(q0 + row) * D + cc * 8) = v;
+      if (q0 + row < Nq) *reinterpret_cast<u32x4*>(Oh + (size_t)(q0 + row) * (size_t)mo.row + cc * 8) = v;
     }
     if (g == 0 && qrow < Nq)
       LSE[(size_t)head * Nq + qrow] = (m_run + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f;

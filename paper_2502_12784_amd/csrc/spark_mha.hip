@@ -15,6 +15,24 @@ using namespace spark;
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Everything one problem is made of; the entry points fill it and hand it to the launchers.
+struct Problem {
+  int B, H, Nq, Nk, d;
+  float scale;
+  int causal;
+  int dtype;
+  int thr;  // dropout threshold, 0 = no dropout
+  unsigned long long seed;
+  unsigned offset;
+  // element strides of the [B,H,N,d] tensors
+  TensorMap mq, mk, mv, mo, mdo, mdq, mdk, mdv;
+  hipStream_t st;
+};
+
+TensorMap contiguous(int H, int N, int d) {
+  return TensorMap{(long long)H * N * d, (long long)N * d, (long long)d};
+}
+
 // Nq queries attend to Nk keys; self-attention passes the same N twice.
 int check_common(int B, int H, int Nq, int Nk, int d, float scale, int causal, int dtype) {
   if (dtype != SPARK_F16 && dtype != SPARK_BF16) return SPARK_ERR_DTYPE;
@@ -26,7 +44,21 @@ int check_common(int B, int H, int Nq, int Nk, int d, float scale, int causal, i
   const int64_t nmax = Nq > Nk ? Nq : Nk;
   const int64_t tiles64 = (nmax + 63) / 64;
   if (bh * tiles64 >= (int64_t)1 << 31) return SPARK_ERR_SHAPE;
-  if (nmax * d >= (int64_t)1 << 31) return SPARK_ERR_SHAPE;
+  // 32-bit byte offsets inside one head, including the rows a ragged last tile reaches past N
+  if ((nmax + 256) * d >= (int64_t)1 << 31) return SPARK_ERR_SHAPE;
+  return SPARK_OK;
+}
+
+// A strided tensor is usable if rows hold d contiguous elements, every stride keeps 16-byte
+// alignment, and one head's rows span less than 4 GiB (the kernels address a head through a
+// 32-bit buffer descriptor).
+int check_strides(const spark_strides_t* s, int N, int d, TensorMap* out) {
+  if (!s) return SPARK_ERR_NULL;
+  if (s->batch < 0 || s->head < 0 || s->row < d) return SPARK_ERR_SHAPE;
+  if ((s->batch | s->head | s->row) & 7) return SPARK_ERR_ALIGN;
+  // 32-bit byte offsets inside one head, including the rows a ragged last tile reaches past N
+  if ((int64_t)(N + 256) * s->row * 2 >= (int64_t)1 << 32) return SPARK_ERR_SHAPE;
+  *out = TensorMap{s->batch, s->head, s->row};
   return SPARK_OK;
 }
 
@@ -57,43 +89,46 @@ int set_smem(KernelT kernel, int bytes) {
 }
 
 template <typename T, int D, bool CAUSAL, bool DROP>
-int launch_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int BH, int Nq,
-               int Nk, float scale, const Dropout& dr, hipStream_t st) {
+int launch_fwd(const Problem& p, const void* Q, const void* K, const void* V, void* O, float* LSE) {
   using C = FwdCfg<D>;
   auto kernel = mha_fwd_kernel<T, D, CAUSAL, DROP>;
   static const int attr = set_smem(kernel, C::SMEM);
   if (attr != SPARK_OK) return attr;
-  const int nqt = (Nq + C::BM - 1) / C::BM;
-  const float scale_log2 = scale * 1.4426950408889634f;
-  hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nqt))), dim3(256), C::SMEM, st,
+  const int BH = p.B * p.H;
+  const int nqt = (p.Nq + C::BM - 1) / C::BM;
+  const float scale_log2 = p.scale * 1.4426950408889634f;
+  hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nqt))), dim3(256), C::SMEM, p.st,
                      static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
-                     static_cast<T*>(O), LSE, Nq, Nk, nqt, scale_log2, dr);
+                     static_cast<T*>(O), LSE, p.mq, p.mk, p.mv, p.mo, p.H, p.Nq, p.Nk, nqt, scale_log2,
+                     make_dropout(p.thr, p.seed, p.offset));
   return hipGetLastError() == hipSuccess ? SPARK_OK : SPARK_ERR_LAUNCH;
 }
 
 template <typename T, int D, bool CAUSAL, bool DROP>
-int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
-               const void* dO, void* dQ, void* dK, void* dV, float* Dws, int BH, int Nq, int Nk,
-               float scale, const Dropout& dr, hipStream_t st, void* const* ev) {
+int launch_bwd(const Problem& p, const void* Q, const void* K, const void* V, const void* O,
+               const float* LSE, const void* dO, void* dQ, void* dK, void* dV, float* Dws,
+               void* const* ev) {
   const T* q = static_cast<const T*>(Q);
   const T* k = static_cast<const T*>(K);
   const T* v = static_cast<const T*>(V);
   const T* o = static_cast<const T*>(O);
   const T* dout = static_cast<const T*>(dO);
-  const float scale_log2 = scale * 1.4426950408889634f;
-  float* LSE2ws = Dws + (size_t)BH * Nq;  // second half of the workspace: LSE * log2(e)
+  const int BH = p.B * p.H;
+  const float scale_log2 = p.scale * 1.4426950408889634f;
+  const Dropout dr = make_dropout(p.thr, p.seed, p.offset);
+  float* LSE2ws = Dws + (size_t)BH * p.Nq;  // second half of the workspace: LSE * log2(e)
   // optional profiling marks between the kernels (spark_mha_bwd_marked)
   auto mark = [&](int i) {
-    return !ev || hipEventRecord(static_cast<hipEvent_t>(ev[i]), st) == hipSuccess;
+    return !ev || hipEventRecord(static_cast<hipEvent_t>(ev[i]), p.st) == hipSuccess;
   };
 
   if (!mark(0)) return SPARK_ERR_LAUNCH;
   {  // D = rowsum(dO o O): one wave per 64/(D/8) rows
     constexpr int ROWS_PER_BLOCK = 256 / (D / 8);
-    const int64_t rows = (int64_t)BH * Nq;
+    const int64_t rows = (int64_t)BH * p.Nq;
     const unsigned grid = (unsigned)((rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK);
-    hipLaunchKernelGGL((mha_bwd_dot_kernel<T, D>), dim3(grid), dim3(256), 0, st, o, dout, LSE, Dws,
-                       LSE2ws, rows, DROP ? dr.keep_prob : 1.0f);
+    hipLaunchKernelGGL((mha_bwd_dot_kernel<T, D>), dim3(grid), dim3(256), 0, p.st, o, dout, LSE, Dws,
+                       LSE2ws, p.mo, p.mdo, p.H, p.Nq, rows, DROP ? dr.keep_prob : 1.0f);
     if (hipGetLastError() != hipSuccess || !mark(1)) return SPARK_ERR_LAUNCH;
   }
   {  // dK, dV: one workgroup per tile of 128 keys, software-pipelined
@@ -101,9 +136,10 @@ int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const
     auto kernel = mha_bwd_dkdv_pipe_kernel<T, D, CAUSAL, DROP>;
     static const int attr = set_smem(kernel, C::SMEM);
     if (attr != SPARK_OK) return attr;
-    const int nkt = (Nk + C::BN - 1) / C::BN;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nkt))), dim3(256), C::SMEM, st, q, k, v, dout,
-                       LSE2ws, Dws, static_cast<T*>(dK), static_cast<T*>(dV), Nq, Nk, nkt, scale, dr);
+    const int nkt = (p.Nk + C::BN - 1) / C::BN;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nkt))), dim3(256), C::SMEM, p.st,
+                       q, k, v, dout, LSE2ws, Dws, static_cast<T*>(dK), static_cast<T*>(dV), p.mq, p.mk,
+                       p.mv, p.mdo, p.mdk, p.mdv, p.H, p.Nq, p.Nk, nkt, p.scale, dr);
     if (hipGetLastError() != hipSuccess || !mark(2)) return SPARK_ERR_LAUNCH;
   }
   {  // dQ: one workgroup per tile of 128 queries
@@ -111,118 +147,141 @@ int launch_bwd(const void* Q, const void* K, const void* V, const void* O, const
     auto kernel = mha_bwd_dq_kernel<T, D, CAUSAL, DROP>;
     static const int attr = set_smem(kernel, C::SMEM);
     if (attr != SPARK_OK) return attr;
-    const int nqt = (Nq + C::BM - 1) / C::BM;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nqt))), dim3(256), C::SMEM, st, q, k, v, dout,
-                       LSE, Dws, static_cast<T*>(dQ), Nq, Nk, nqt, scale, scale_log2, dr);
+    const int nqt = (p.Nq + C::BM - 1) / C::BM;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nqt))), dim3(256), C::SMEM, p.st,
+                       q, k, v, dout, LSE, Dws, static_cast<T*>(dQ), p.mq, p.mk, p.mv, p.mdo, p.mdq, p.H,
+                       p.Nq, p.Nk, nqt, p.scale, scale_log2, dr);
     if (hipGetLastError() != hipSuccess || !mark(3)) return SPARK_ERR_LAUNCH;
   }
   return SPARK_OK;
 }
 
 // Expand the (dtype, d, causal, dropout) runtime tuple into a template instantiation.
-#define SPARK_DISPATCH_CD(FN, T, D, ...)                                               \
-  do {                                                                                 \
-    if (causal) return drop ? FN<T, D, true, true>(__VA_ARGS__)                        \
-                            : FN<T, D, true, false>(__VA_ARGS__);                      \
-    return drop ? FN<T, D, false, true>(__VA_ARGS__) : FN<T, D, false, false>(__VA_ARGS__); \
+#define SPARK_DISPATCH_CD(FN, T, D, ...)                                                    \
+  do {                                                                                      \
+    if (p.causal) return p.thr ? FN<T, D, true, true>(__VA_ARGS__)                          \
+                               : FN<T, D, true, false>(__VA_ARGS__);                        \
+    return p.thr ? FN<T, D, false, true>(__VA_ARGS__) : FN<T, D, false, false>(__VA_ARGS__); \
   } while (0)
-#define SPARK_DISPATCH(FN, ...)                                                        \
-  do {                                                                                 \
-    if (dtype == SPARK_F16) {                                                          \
-      if (d == 64) SPARK_DISPATCH_CD(FN, _Float16, 64, __VA_ARGS__);                   \
-      SPARK_DISPATCH_CD(FN, _Float16, 128, __VA_ARGS__);                               \
-    }                                                                                  \
-    if (d == 64) SPARK_DISPATCH_CD(FN, __bf16, 64, __VA_ARGS__);                       \
-    SPARK_DISPATCH_CD(FN, __bf16, 128, __VA_ARGS__);                                   \
+#define SPARK_DISPATCH(FN, ...)                                              \
+  do {                                                                       \
+    if (p.dtype == SPARK_F16) {                                              \
+      if (p.d == 64) SPARK_DISPATCH_CD(FN, _Float16, 64, __VA_ARGS__);       \
+      SPARK_DISPATCH_CD(FN, _Float16, 128, __VA_ARGS__);                     \
+    }                                                                        \
+    if (p.d == 64) SPARK_DISPATCH_CD(FN, __bf16, 64, __VA_ARGS__);           \
+    SPARK_DISPATCH_CD(FN, __bf16, 128, __VA_ARGS__);                         \
   } while (0)
+
+// Shape, scale, dtype and dropout checks common to forward and backward; fills `p` with
+// contiguous strides (the strided entry points overwrite them afterwards).
+int make_problem(Problem* p, int B, int H, int Nq, int Nk, int d, float scale, int causal, int thr,
+                 unsigned long long seed, unsigned offset, spark_dtype_t dtype, void* stream) {
+  const int rc = check_common(B, H, Nq, Nk, d, scale, causal, (int)dtype);
+  if (rc != SPARK_OK) return rc;
+  if (thr < 0) return SPARK_ERR_SHAPE;
+  p->B = B; p->H = H; p->Nq = Nq; p->Nk = Nk; p->d = d;
+  p->scale = scale;
+  p->causal = causal != 0;
+  p->dtype = (int)dtype;
+  p->thr = thr;
+  p->seed = seed;
+  p->offset = offset;
+  p->mq = p->mo = p->mdo = p->mdq = contiguous(H, Nq, d);
+  p->mk = p->mv = p->mdk = p->mdv = contiguous(H, Nk, d);
+  p->st = static_cast<hipStream_t>(stream);
+  return SPARK_OK;
+}
+
+int run_fwd(const Problem& p, const void* Q, const void* K, const void* V, void* O, float* LSE) {
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE))
+    return SPARK_ERR_ALIGN;
+  SPARK_DISPATCH(launch_fwd, p, Q, K, V, O, LSE);
+}
+
+size_t workspace_bytes(int B, int H, int Nq) { return 2 * (size_t)B * H * Nq * sizeof(float); }
+
+int run_bwd(const Problem& p, const void* Q, const void* K, const void* V, const void* O,
+            const float* LSE, const void* dO, void* dQ, void* dK, void* dV, void* workspace,
+            size_t ws_bytes, void* const* ev) {
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE) ||
+      !aligned16(dO) || !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
+    return SPARK_ERR_ALIGN;
+  if (ws_bytes < workspace_bytes(p.B, p.H, p.Nq)) return SPARK_ERR_WORKSPACE;
+  float* Dws = static_cast<float*>(workspace);
+  SPARK_DISPATCH(launch_bwd, p, Q, K, V, O, LSE, dO, dQ, dK, dV, Dws, ev);
+}
 
 }  // namespace
 
 extern "C" {
 
-static int fwd_impl(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H,
-                    int Nq, int Nk, int d, float scale, int causal, int thr,
-                    unsigned long long seed, unsigned offset, spark_dtype_t dtype_e, void* stream) {
-  const int dtype = (int)dtype_e;
-  if (!Q || !K || !V || !O || !LSE) return SPARK_ERR_NULL;
-  const int rc = check_common(B, H, Nq, Nk, d, scale, causal, dtype);
-  if (rc != SPARK_OK) return rc;
-  if (thr < 0) return SPARK_ERR_SHAPE;
-  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE))
-    return SPARK_ERR_ALIGN;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  const int BH = B * H;
-  const bool drop = thr > 0;
-  const Dropout dr = make_dropout(thr, seed, offset);
-  SPARK_DISPATCH(launch_fwd, Q, K, V, O, LSE, BH, Nq, Nk, scale, dr, st);
-}
-
 int spark_mha_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B, int H,
                   int N, int d, float scale, int causal, spark_dtype_t dtype, void* stream) {
-  return fwd_impl(Q, K, V, O, LSE, B, H, N, N, d, scale, causal, 0, 0, 0, dtype, stream);
+  return spark_mha_cross_fwd(Q, K, V, O, LSE, B, H, N, N, d, scale, causal, dtype, stream);
 }
 
 int spark_mha_cross_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
                         int H, int Nq, int Nk, int d, float scale, int causal,
                         spark_dtype_t dtype, void* stream) {
-  return fwd_impl(Q, K, V, O, LSE, B, H, Nq, Nk, d, scale, causal, 0, 0, 0, dtype, stream);
+  return spark_mha_dropout_fwd(Q, K, V, O, LSE, B, H, Nq, Nk, d, scale, causal, 0.0f, 0, 0, dtype,
+                               stream);
 }
 
 int spark_mha_dropout_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE, int B,
                           int H, int Nq, int Nk, int d, float scale, int causal, float p_drop,
                           unsigned long long seed, unsigned offset, spark_dtype_t dtype,
                           void* stream) {
-  return fwd_impl(Q, K, V, O, LSE, B, H, Nq, Nk, d, scale, causal, drop_threshold(p_drop), seed,
-                  offset, dtype, stream);
+  if (!Q || !K || !V || !O || !LSE) return SPARK_ERR_NULL;
+  Problem p;
+  const int rc = make_problem(&p, B, H, Nq, Nk, d, scale, causal, drop_threshold(p_drop), seed,
+                              offset, dtype, stream);
+  if (rc != SPARK_OK) return rc;
+  return run_fwd(p, Q, K, V, O, LSE);
+}
+
+int spark_mha_strided_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                          const spark_strides_t* sQ, const spark_strides_t* sK,
+                          const spark_strides_t* sV, const spark_strides_t* sO, int B, int H, int Nq,
+                          int Nk, int d, float scale, int causal, float p_drop,
+                          unsigned long long seed, unsigned offset, spark_dtype_t dtype,
+                          void* stream) {
+  if (!Q || !K || !V || !O || !LSE) return SPARK_ERR_NULL;
+  Problem p;
+  int rc = make_problem(&p, B, H, Nq, Nk, d, scale, causal, drop_threshold(p_drop), seed, offset,
+                        dtype, stream);
+  if (rc != SPARK_OK) return rc;
+  if ((rc = check_strides(sQ, Nq, d, &p.mq)) != SPARK_OK) return rc;
+  if ((rc = check_strides(sK, Nk, d, &p.mk)) != SPARK_OK) return rc;
+  if ((rc = check_strides(sV, Nk, d, &p.mv)) != SPARK_OK) return rc;
+  if ((rc = check_strides(sO, Nq, d, &p.mo)) != SPARK_OK) return rc;
+  return run_fwd(p, Q, K, V, O, LSE);
 }
 
 size_t spark_mha_cross_bwd_workspace_bytes(int B, int H, int Nq, int Nk, int d,
                                            spark_dtype_t dtype) {
   if (check_common(B, H, Nq, Nk, d, 1.0f, 0, (int)dtype) != SPARK_OK) return 0;
-  return 2 * (size_t)B * H * Nq * sizeof(float);  // D and LSE*log2(e), fp32 [B,H,Nq] each
+  return workspace_bytes(B, H, Nq);  // D and LSE*log2(e), fp32 [B,H,Nq] each
 }
 
 size_t spark_mha_bwd_workspace_bytes(int B, int H, int N, int d, spark_dtype_t dtype) {
   return spark_mha_cross_bwd_workspace_bytes(B, H, N, N, d, dtype);
 }
 
-static int bwd_impl(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
-                    const void* dO, void* dQ, void* dK, void* dV, void* workspace,
-                    size_t workspace_bytes, int B, int H, int Nq, int Nk, int d, float scale,
-                    int causal, int thr, unsigned long long seed, unsigned offset,
-                    spark_dtype_t dtype_e, void* stream, void* const* ev) {
-  const int dtype = (int)dtype_e;
-  if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV || !workspace) return SPARK_ERR_NULL;
-  const int rc = check_common(B, H, Nq, Nk, d, scale, causal, dtype);
-  if (rc != SPARK_OK) return rc;
-  if (thr < 0) return SPARK_ERR_SHAPE;
-  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE) ||
-      !aligned16(dO) || !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
-    return SPARK_ERR_ALIGN;
-  if (workspace_bytes < spark_mha_cross_bwd_workspace_bytes(B, H, Nq, Nk, d, dtype_e))
-    return SPARK_ERR_WORKSPACE;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  const int BH = B * H;
-  float* Dws = static_cast<float*>(workspace);
-  const bool drop = thr > 0;
-  const Dropout dr = make_dropout(thr, seed, offset);
-  SPARK_DISPATCH(launch_bwd, Q, K, V, O, LSE, dO, dQ, dK, dV, Dws, BH, Nq, Nk, scale, dr, st, ev);
-}
-
 int spark_mha_bwd(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
                   const void* dO, void* dQ, void* dK, void* dV, void* workspace,
                   size_t workspace_bytes, int B, int H, int N, int d, float scale, int causal,
                   spark_dtype_t dtype, void* stream) {
-  return bwd_impl(Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, B, H, N, N, d,
-                  scale, causal, 0, 0, 0, dtype, stream, nullptr);
+  return spark_mha_cross_bwd(Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, B, H, N, N,
+                             d, scale, causal, dtype, stream);
 }
 
 int spark_mha_cross_bwd(const void* Q, const void* K, const void* V, const void* O,
                         const float* LSE, const void* dO, void* dQ, void* dK, void* dV,
                         void* workspace, size_t workspace_bytes, int B, int H, int Nq, int Nk,
                         int d, float scale, int causal, spark_dtype_t dtype, void* stream) {
-  return bwd_impl(Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, B, H, Nq, Nk, d,
-                  scale, causal, 0, 0, 0, dtype, stream, nullptr);
+  return spark_mha_dropout_bwd(Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, B, H, Nq,
+                               Nk, d, scale, causal, 0.0f, 0, 0, dtype, stream);
 }
 
 int spark_mha_dropout_bwd(const void* Q, const void* K, const void* V, const void* O,
@@ -230,8 +289,37 @@ int spark_mha_dropout_bwd(const void* Q, const void* K, const void* V, const voi
                           void* workspace, size_t workspace_bytes, int B, int H, int Nq, int Nk,
                           int d, float scale, int causal, float p_drop, unsigned long long seed,
                           unsigned offset, spark_dtype_t dtype, void* stream) {
-  return bwd_impl(Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, B, H, Nq, Nk, d,
-                  scale, causal, drop_threshold(p_drop), seed, offset, dtype, stream, nullptr);
+  if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV || !workspace) return SPARK_ERR_NULL;
+  Problem p;
+  const int rc = make_problem(&p, B, H, Nq, Nk, d, scale, causal, drop_threshold(p_drop), seed,
+                              offset, dtype, stream);
+  if (rc != SPARK_OK) return rc;
+  return run_bwd(p, Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, nullptr);
+}
+
+int spark_mha_strided_bwd(const void* Q, const void* K, const void* V, const void* O,
+                          const float* LSE, const void* dO, void* dQ, void* dK, void* dV,
+                          const spark_strides_t* sQ, const spark_strides_t* sK,
+                          const spark_strides_t* sV, const spark_strides_t* sO,
+                          const spark_strides_t* sdO, const spark_strides_t* sdQ,
+                          const spark_strides_t* sdK, const spark_strides_t* sdV, void* workspace,
+                          size_t workspace_bytes, int B, int H, int Nq, int Nk, int d, float scale,
+                          int causal, float p_drop, unsigned long long seed, unsigned offset,
+                          spark_dtype_t dtype, void* stream) {
+  if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV || !workspace) return SPARK_ERR_NULL;
+  Problem p;
+  int rc = make_problem(&p, B, H, Nq, Nk, d, scale, causal, drop_threshold(p_drop), seed, offset,
+                        dtype, stream);
+  if (rc != SPARK_OK) return rc;
+  if ((rc = check_strides(sQ, Nq, d, &p.mq)) != SPARK_OK) return rc;
+  if ((rc = check_strides(sK, Nk, d, &p.mk)) != SPARK_OK) return rc;
+  if ((rc = check_strides(sV, Nk, d, &p.mv)) != SPARK_OK) return rc;
+  if ((rc = check_strides(sO, Nq, d, &p.mo)) != SPARK_OK) return rc;
+  if ((rc = check_strides(sdO, Nq, d, &p.mdo)) != SPARK_OK) return rc;
+  if ((rc = check_strides(sdQ, Nq, d, &p.mdq)) != SPARK_OK) return rc;
+  if ((rc = check_strides(sdK, Nk, d, &p.mdk)) != SPARK_OK) return rc;
+  if ((rc = check_strides(sdV, Nk, d, &p.mdv)) != SPARK_OK) return rc;
+  return run_bwd(p, Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, nullptr);
 }
 
 int spark_mha_bwd_marked(const void* Q, const void* K, const void* V, const void* O,
@@ -239,9 +327,12 @@ int spark_mha_bwd_marked(const void* Q, const void* K, const void* V, const void
                          void* workspace, size_t workspace_bytes, int B, int H, int N, int d,
                          float scale, int causal, spark_dtype_t dtype, void* stream,
                          void* const events[4]) {
+  if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV || !workspace) return SPARK_ERR_NULL;
   if (!events || !events[0] || !events[1] || !events[2] || !events[3]) return SPARK_ERR_NULL;
-  return bwd_impl(Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, B, H, N, N, d,
-                  scale, causal, 0, 0, 0, dtype, stream, events);
+  Problem p;
+  const int rc = make_problem(&p, B, H, N, N, d, scale, causal, 0, 0, 0, dtype, stream);
+  if (rc != SPARK_OK) return rc;
+  return run_bwd(p, Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, events);
 }
 
 int spark_dropout_threshold(float p_drop) { return drop_threshold(p_drop); }
@@ -265,9 +356,11 @@ const char* spark_status_str(int status) {
   switch (status) {
     case SPARK_OK: return "ok";
     case SPARK_ERR_NULL: return "a required pointer is NULL";
-    case SPARK_ERR_SHAPE: return "unsupported shape or scale (need B,H,N >= 1, d in {64,128}, finite scale > 0, Nq == Nk if causal, 0 <= p_drop < 0.998)";
+    case SPARK_ERR_SHAPE:
+      return "unsupported shape, scale, dropout rate or stride (need B,H,N >= 1, d in {64,128}, finite "
+             "scale > 0, Nq == Nk if causal, 0 <= p_drop < 0.998, row stride >= d)";
     case SPARK_ERR_DTYPE: return "unsupported dtype (need SPARK_F16 or SPARK_BF16)";
-    case SPARK_ERR_ALIGN: return "a pointer is not 16-byte aligned";
+    case SPARK_ERR_ALIGN: return "a pointer or stride is not 16-byte aligned";
     case SPARK_ERR_WORKSPACE: return "workspace smaller than spark_mha_bwd_workspace_bytes()";
     case SPARK_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
     default: return "unknown status";

@@ -15,6 +15,23 @@ static __device__ __forceinline__ int xcd_contiguous(int id, int total) {
   return base + slot;
 }
 
+// Where one [B, H, N, d] tensor lives: element strides of the batch, head and row (sequence)
+// indices; the d elements of a row are contiguous.  [B,H,N,d] contiguous is {H*N*d, N*d, d};
+// a [B,N,H,d] buffer viewed as [B,H,N,d] is {N*H*d, d, H*d}.
+struct TensorMap {
+  long long batch, head, row;
+};
+// Element offset of (batch, head) = flat index `bh` of B*H.
+static __device__ __forceinline__ size_t head_base(const TensorMap& m, int bh, int H) {
+  const int b = bh / H, h = bh - b * H;
+  return (size_t)b * (size_t)m.batch + (size_t)h * (size_t)m.head;
+}
+// Bytes a buffer view of one head must span: rows 0..n-1, the last one d elements long.
+template <int D>
+static __device__ __forceinline__ uint32_t head_span_bytes(const TensorMap& m, int n) {
+  return (uint32_t)(((size_t)(n - 1) * (size_t)m.row + D) * 2);
+}
+
 // Work items per head for a kernel that walks `tiles` tiles: causal kernels pair tile p with
 // tile tiles-1-p.
 template <bool CAUSAL>
@@ -81,28 +98,31 @@ static __device__ __forceinline__ typename Frag<T>::v8 read_tr_pair(SPARK_LDS co
 // blocks w, w+4, ... of the tile; lane l writes bytes [16 l, 16 l + 16) of its block, so it
 // fetches the logical chunk that the swizzle places there.  `lane_src` is that per-lane source
 // offset for block `wave` (the later blocks are a multiple of 16 rows further on, where the
-// swizzle repeats).  Rows past the end of the matrix arrive as zeros.
+// swizzle repeats).  Rows past the end of the matrix arrive as zeros.  `row_bytes` is the
+// distance between consecutive rows in global memory (2*D when the rows are contiguous).
 template <int D>
-static __device__ __forceinline__ uint32_t dma_lane_src(int wave, int lane) {
+static __device__ __forceinline__ uint32_t dma_lane_src(int wave, int lane, uint32_t row_bytes) {
   const int byte = wave * 1024 + lane * 16;
   const int row = byte / (2 * D), pc = (byte % (2 * D)) >> 4;
-  return (uint32_t)(row * (2 * D) + ((pc ^ swz<D>(row)) << 4));
+  return (uint32_t)row * row_bytes + (uint32_t)((pc ^ swz<D>(row)) << 4);
 }
 template <int D, int ROWS>
 static __device__ __forceinline__ void tile_dma(const BufView& view, int r0, SPARK_LDS char* dst,
-                                                int wave, uint32_t lane_src) {
-  static_assert((4 * 1024 / (2 * D)) % 16 == 0, "blocks of one wave must be 16 rows apart");
+                                                int wave, uint32_t lane_src, uint32_t row_bytes) {
+  constexpr int RPG = 4 * 1024 / (2 * D);  // rows covered by one 1 KB block of each of the 4 waves
+  static_assert(RPG % 16 == 0, "blocks of one wave must be 16 rows apart");
 #pragma unroll
   for (int i = 0; i < ROWS * 2 * D / 4096; ++i)
-    view.load16_to_lds(dst + (i * 4 + wave) * 1024, lane_src, (uint32_t)r0 * (2 * D) + i * 4096);
+    view.load16_to_lds(dst + (i * 4 + wave) * 1024, lane_src, (uint32_t)(r0 + i * RPG) * row_bytes);
 }
 
 // Write a wave's transposed accumulator (D x 32, lane = column) times `mul` as 32 rows of D
-// 16-bit values: through the wave's LDS slice `ob`, then 16-byte row stores for rows < N.
+// 16-bit values: through the wave's LDS slice `ob`, then 16-byte row stores for rows < N
+// (`row_stride` elements apart).
 template <typename T, int D, int OSTR>
 static __device__ __forceinline__ void store_transposed(const f32x16 (&acc)[D / 32], float mul,
                                                         SPARK_LDS char* ob, T* __restrict__ out,
-                                                        int row0, int N, int lane) {
+                                                        int row0, int N, int lane, size_t row_stride) {
   using v4 = typename Frag<T>::v4;
   constexpr int CPR = D / 8;
   constexpr int RPP = 64 / CPR;
@@ -120,7 +140,7 @@ static __device__ __forceinline__ void store_transposed(const f32x16 (&acc)[D / 
   for (int p = 0; p < 32 / RPP; ++p) {
     const int row = p * RPP + lane / CPR, cc = lane % CPR;
     const u32x4 v = lds_read16<u32x4>(ob, row * OSTR + cc * 16);
-    if (row0 + row < N) *reinterpret_cast<u32x4*>(out + (size_t)(row0 + row) * D + cc * 8) = v;
+    if (row0 + row < N) *reinterpret_cast<u32x4*>(out + (size_t)(row0 + row) * row_stride + cc * 8) = v;
   }
 }
 

@@ -142,6 +142,28 @@ def test_dropout_validation(lib):
     assert lib.spark_dropout_mask(0x1000, 1, 1, 4, 4, 2.0, 1, 0, None) == E_SHAPE
 
 
+def test_strided_validation(lib):
+    S = pkg.Strides
+
+    def fwd(sq=S(128 * 64, 64 * 128, 64), so=S(128 * 64, 64 * 128, 64), sk=S(128 * 64, 64 * 128, 64), N=128, d=64):
+        return lib.spark_mha_strided_fwd(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, sq, sk, sk, so, 1, 1, N, N,
+                                         d, 0.125, 0, 0.0, 0, 0, 0, None)
+
+    assert fwd(sq=None) == E_NULL
+    assert fwd(sq=S(0, 0, 32)) == E_SHAPE              # rows would overlap: row stride < d
+    assert fwd(sq=S(-8, 0, 64)) == E_SHAPE
+    assert fwd(sk=S(0, 0, 68)) == E_ALIGN              # 136-byte rows
+    assert fwd(so=S(4, 0, 64)) == E_ALIGN
+    assert fwd(sq=S(0, 0, 1 << 24), N=1024) == E_SHAPE  # one head would span 4 GiB or more
+    eight = [S(128 * 64, 64 * 128, 64)] * 8
+    args = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000, 0x8000, 0x9000]
+    tail = [0xA000, 1 << 20, 1, 1, 128, 128, 64, 0.125, 0, 0.0, 0, 0, 0, None]
+    assert lib.spark_mha_strided_bwd(*args, *eight[:7], None, *tail) == E_NULL
+    assert lib.spark_mha_strided_bwd(*args, *eight[:7], S(0, 0, 8), *tail) == E_SHAPE
+    tail[1] = 8
+    assert lib.spark_mha_strided_bwd(*args, *eight, *tail) == E_WS
+
+
 def test_workspace_bytes(lib):
     assert pkg.spark_mha_bwd_workspace_bytes(4, 16, 4096, 128, 1) == 2 * 4 * 16 * 4096 * 4
     assert pkg.spark_mha_bwd_workspace_bytes(4, 16, 4096, 100, 1) == 0
