@@ -93,7 +93,7 @@ template <int D> struct BwdKvPipeCfg {
 };
 
 template <typename T, int D, bool CAUSAL, bool DROP>
-__global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_pipe_kernel(
+__global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_pipe_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ dO, const float* __restrict__ LSE2, const float* __restrict__ Dws,
     T* __restrict__ dK, T* __restrict__ dV, TensorMap mq, TensorMap mk, TensorMap mv, TensorMap mdo,
@@ -294,7 +294,9 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_pipe_kernel
       auto step = [&](f32x16& s_new, f32x16& dp_new, int sub_new, int q0_new, int sub_cur, int q0_cur) {
         // ---- region 1: scores of the next step  ||  second half of P, dS of the current step ----
         float p[8], ds[8];
-        if (DROP) keep_bytes_key_lane(dr, head, krow, q0_new, lane, kbNew);
+        // dropout decisions of the next step: the ten generator rounds ride in the MFMA slots below
+        Philox rng;
+        if (DROP) rng = keep_key_lane_begin(dr, head, krow, q0_new, lane);
         load_stats(lL, dL, sub_new, 0);
         load_tgroup(0, sub_cur);
 #pragma unroll
@@ -310,8 +312,14 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mha_bwd_dkdv_pipe_kernel
 #pragma unroll
             for (int x = 0; x < E1; ++x) softmax_elem(sV, dpV, 1, (i / 2) * E1 + x, lH, dH, q0_cur, mask, kbCur, p, ds);
           }
+          if (DROP) {
+#pragma unroll
+            for (int round = i * 10 / (4 * NG); round < (i + 1) * 10 / (4 * NG); ++round)
+              philox_round(rng, dr.key0, dr.key1, round);
+          }
           sched_fence();
         }
+        if (DROP) keep_key_lane_finish(rng, lane, kbNew);
         const v8 pfH = pack8<T>(p), dsfH = pack8<T>(ds);
         load_stats(lH, dH, sub_new, 1);
         sched_fence();

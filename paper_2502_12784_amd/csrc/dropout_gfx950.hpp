@@ -26,23 +26,28 @@ struct Dropout {
   float rescale;        // 256 / (256 - thr)
 };
 
-// Philox4x32-10.  The key schedule is uniform across the wave and lives in scalar registers.
+// Philox4x32-10, one round at a time so that a kernel can place the rounds between its MFMAs.
+// The key schedule (key + round * Weyl constant) is uniform across the wave: scalar registers.
+struct Philox {
+  uint32_t c0, c1, c2, c3;
+};
+static __device__ __forceinline__ void philox_round(Philox& s, uint32_t key0, uint32_t key1, int round) {
+  const uint32_t k0 = key0 + (uint32_t)round * 0x9E3779B9u, k1 = key1 + (uint32_t)round * 0xBB67AE85u;
+  const uint64_t p0 = (uint64_t)0xD2511F53u * s.c0;
+  const uint64_t p1 = (uint64_t)0xCD9E8D57u * s.c2;
+  const uint32_t n0 = (uint32_t)(p1 >> 32) ^ s.c1 ^ k0;
+  const uint32_t n2 = (uint32_t)(p0 >> 32) ^ s.c3 ^ k1;
+  s.c1 = (uint32_t)p1;
+  s.c3 = (uint32_t)p0;
+  s.c0 = n0;
+  s.c2 = n2;
+}
 static __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                                      uint32_t k0, uint32_t k1, uint32_t (&out)[4]) {
+  Philox s{c0, c1, c2, c3};
 #pragma unroll
-  for (int round = 0; round < 10; ++round) {
-    const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
-    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
-    c1 = (uint32_t)p1;
-    c3 = (uint32_t)p0;
-    c0 = n0;
-    c2 = n2;
-    k0 += 0x9E3779B9u;
-    k1 += 0xBB67AE85u;
-  }
-  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+  for (int round = 0; round < 10; ++round) philox_round(s, k0, k1, round);
+  out[0] = s.c0; out[1] = s.c1; out[2] = s.c2; out[3] = s.c3;
 }
 
 // value of `v` in lane A of this lane's quad (all four lanes must be active)
@@ -70,15 +75,27 @@ static __device__ __forceinline__ void keep_bytes_query_lane(const Dropout& dr, 
   kb[3] = own_row(quad_bcast<3>(x[0]), quad_bcast<3>(x[1]), quad_bcast<3>(x[2]), quad_bcast<3>(x[3]));
 }
 
-// Lane = key column (S layouts of the dK/dV kernels).  The lane's key is `krow`
+// Lane = key column (S layouts of the dK/dV kernel).  The lane's key is `krow`
 // (krow mod 4 == lane mod 4) and it holds queries qblk + 8a + 4g + b of the 32-query block
 // starting at qblk (a multiple of 32).  kb[a] as above: byte b belongs to register 4a + b.
+// In three parts (counter, ten rounds of philox_round, exchange) so that the kernel can spread
+// the rounds over its MFMA slots; keep_bytes_key_lane runs them back to back.
+static __device__ __forceinline__ Philox keep_key_lane_begin(const Dropout& dr, int head, int krow, int qblk,
+                                                             int lane) {
+  const int w = lane & 3, g = lane >> 5;  // this lane evaluates the call of strip a = w
+  return Philox{(uint32_t)(krow >> 2), (uint32_t)((qblk >> 2) + 2 * w + g), (uint32_t)head, dr.offset};
+}
+static __device__ __forceinline__ void keep_key_lane_finish(const Philox& s, int lane, uint32_t (&kb)[4]);
 static __device__ __forceinline__ void keep_bytes_key_lane(const Dropout& dr, int head, int krow,
                                                            int qblk, int lane, uint32_t (&kb)[4]) {
-  const int w = lane & 3, g = lane >> 5;
-  uint32_t x[4];
-  philox4x32_10((uint32_t)(krow >> 2), (uint32_t)((qblk >> 2) + 2 * w + g), (uint32_t)head, dr.offset,
-                dr.key0, dr.key1, x);  // this lane evaluates the call of strip a = w
+  Philox s = keep_key_lane_begin(dr, head, krow, qblk, lane);
+#pragma unroll
+  for (int round = 0; round < 10; ++round) philox_round(s, dr.key0, dr.key1, round);
+  keep_key_lane_finish(s, lane, kb);
+}
+static __device__ __forceinline__ void keep_key_lane_finish(const Philox& s, int lane, uint32_t (&kb)[4]) {
+  const int w = lane & 3;
+  const uint32_t x[4] = {s.c0, s.c1, s.c2, s.c3};
   // byte (key mod 4) of each of the four words (queries) of a call, gathered into one word
   const uint32_t sel_lo = 0x0c0c0400u + 0x0101u * (uint32_t)w;  // v_perm: bytes {w of S1, w of S0, 0, 0}
   auto own_col = [&](uint32_t x0, uint32_t x1, uint32_t x2, uint32_t x3) {
