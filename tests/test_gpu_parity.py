@@ -79,6 +79,24 @@ def test_full_size_configs_sampled_heads(name):
         assert np.isfinite(pu.to_f64(gpu[n])).all(), n
 
 
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+def test_many_heads_ragged_wide_workgroups(dtype, causal):
+    """Enough (batch, head) pairs at d = 128 for the forward to pick its 256-query workgroups, with a
+    sequence length that is a multiple of neither 256 nor 64; sampled heads against the oracle."""
+    B, H, N, d = 16, 16, 600, 128
+    inp = synth.make_inputs(B, H, N, d, dtype, seed=600 + int(causal))
+    scale = 1.0 / math.sqrt(d)
+    gpu = pu.run_gpu(inp, dtype, scale, causal)
+    heads = [0, 77, B * H - 1]
+    ref = pu.run_oracle(inp, dtype, scale, causal, heads=heads)
+    m = pu.compare(gpu, ref, dtype, heads=heads)
+    print(f"\n[parity] wide workgroups N={N} {dtype} causal={causal}: {m}", flush=True)
+    pu.assert_within_tolerance(m, ("wide", dtype, causal))
+    for n in ("O", "LSE", "dQ", "dK", "dV"):
+        assert np.isfinite(pu.to_f64(gpu[n])).all(), n
+
+
 def test_bitwise_reproducible():
     """No atomics anywhere: two runs give identical bits."""
     import torch
