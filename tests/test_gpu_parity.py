@@ -1,7 +1,9 @@
 """GPU parity: HIP path (through the C ABI) against the fp64 CPU oracle, same seeded inputs.
 
 Bar: |O - O_ref| <= 2e-3 + half an output ulp at |O_ref| (the output is rounded once to
-fp16/bf16; 2e-3 bounds the computational error), |LSE - LSE_ref| <= 2e-3, and relative L2
+fp16/bf16) + u * P|V| (P is rounded to the 16-bit operand type before O = P V; u = 2^-8 bf16,
+2^-11 fp16; see parity_util), so 2e-3 bounds the rest of the computational error;
+|LSE - LSE_ref| <= 2e-3, and relative L2
 error <= 1e-2 for each of dQ, dK, dV.
 """
 import math
