@@ -49,9 +49,7 @@ template <int D, int NW = 4> struct FwdCfg {
 };
 
 template <typename T, int D, bool CAUSAL, bool DROP, int NW = 4>
-// Workgroups per CU the register budget is set for: the d = 64 non-causal kernel fits 128
-// registers without spilling, i.e. four waves per SIMD (measured -2.6 % against the default).
-__global__ __launch_bounds__(64 * NW, NW == 4 ? (D == 64 && !CAUSAL && !DROP ? 4 : 2) : 1) void mha_fwd_kernel(
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void mha_fwd_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     T* __restrict__ O, float* __restrict__ LSE, TensorMap mq, TensorMap mk, TensorMap mv,
     TensorMap mo, int H, int Nq, int Nk, int nqt, float scale_log2, Dropout dr) {
@@ -122,7 +120,9 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? (D == 64 && !CAUSAL && !DROP ? 4
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
-    float m_run = -INFINITY;  // running row max (log2 domain)
+    // reference of the row's exponentials (log2 domain).  Finite, so that a masked score (-inf)
+    // minus the reference is -inf and not NaN before the first valid key has set it.
+    float m_run = -1e30f;
     float l_run = 0.f;        // running row sum over this lane's keys only (halves merged at the end)
 
     fetch_tile(0, 0);
@@ -174,8 +174,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? (D == 64 && !CAUSAL && !DROP ? 4
 
         const bool need_mask = (CAUSAL && k0 + C::BN - 1 > q0) || (k0 + C::BN > Nk);
         float t[32];
-        // raw scores of one half -> t, masked; returns the scaled row maximum of the half
-        auto half_max = [&](int h) {
+        // raw scores of one half -> t, masked
+        auto load_half = [&](int h) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) t[h * 16 + r] = s[h][r];
           if (need_mask) {
@@ -186,10 +186,31 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? (D == 64 && !CAUSAL && !DROP ? 4
               if (!ok) t[h * 16 + r] = -INFINITY;
             }
           }
+        };
+        // Online softmax (Eq. 3) with a lazy reference point.  P is formed against the current
+        // reference m_run straight away, WITHOUT computing the row maximum first; the row sum of the
+        // result (needed anyway) tells whether the reference was too low: if no lane's partial sum
+        // exceeds 2^8, no P exceeds 2^8 either, which fp32 sums and the 16-bit MFMA operand hold
+        // without loss, and the reference stays (the final O = acc / l and LSE = m + log l do not
+        // depend on it).  Otherwise (the first tile, and afterwards only when a row's maximum grows
+        // by more than ~2^8) the maximum is computed after all, the reference moved there, the
+        // accumulators rescaled by exp(m_pre - m_cur) as in Eq. 3, and the half's P formed again.
+        // Returns the rescale factor.
+        auto renorm = [&](int h) {
+          load_half(h);  // raw scores again (they are still in the accumulators)
           float mx = t[h * 16];
 #pragma unroll
           for (int r = 1; r < 16; ++r) mx = fmaxf(mx, t[h * 16 + r]);
-          return half_pair_max(mx) * scale_log2;  // scale > 0 commutes with the maximum
+          mx = half_pair_max(mx) * scale_log2;  // scale > 0 commutes with the maximum
+          const float m_new = fmaxf(m_run, mx);
+          const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+          m_run = m_new;
+          l_run *= alpha;
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+          return alpha;
         };
         // Dropout acts on P after the row sums are taken: dropped entries become zero in the
         // operand of O += P V; the survivors' factor 1/(1-p) is applied once, to O, at the end.
@@ -200,8 +221,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? (D == 64 && !CAUSAL && !DROP ? 4
           for (int r = 0; r < 16; ++r)
             if (!keep_reg(kb, r, dr.thr)) t[h * 16 + r] = 0.f;
         };
-        float rs = 0.f;
-        auto exp_elem = [&](int i) {
+        float rs0 = 0.f, rs1 = 0.f;  // this lane's sums of P over the two halves
+        auto exp_elem = [&](int i, float& rs) {
           t[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(t[i], scale_log2, -m_run));
           rs += t[i];
         };
@@ -220,24 +241,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? (D == 64 && !CAUSAL && !DROP ? 4
         load_vgroup(0);
         sched_fence();
 
-        // Online softmax (Eq. 3) with a lazy reference point: m_run is only moved, and the
-        // accumulators only rescaled by exp(m_pre - m_cur), when some row's maximum grew by more
-        // than 2^8.  Until then P is formed against the old reference and stays <= 256, which fp32
-        // sums and the 16-bit MFMA operand hold without loss; the final O = acc / l and
-        // LSE = m + log l do not depend on which reference was used.
-        {
-          const float mx = half_max(0);
-          if (__any(mx > m_run + 8.0f)) {
-            const float m_new = fmaxf(m_run, mx);
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-            m_run = m_new;
-            l_run *= alpha;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-              for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
-          }
-        }
+        load_half(0);
         // ---- S_1  ||  exponentials of half 0 ----
         constexpr int EPU = 16 / KS;  // elements per MFMA
 #pragma unroll
@@ -246,30 +250,20 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? (D == 64 && !CAUSAL && !DROP ? 4
           for (int e = 0; e < 4; ++e) {
             s[1] = F::mfma(kf[gi & 1][e], qf[4 * (gi - GPH) + e], s[1]);
 #pragma unroll
-            for (int x = 0; x < EPU; ++x) exp_elem(((gi - GPH) * 4 + e) * EPU + x);
+            for (int x = 0; x < EPU; ++x) exp_elem(((gi - GPH) * 4 + e) * EPU + x, rs0);
             sched_fence();
           }
           if (gi + 2 < 2 * GPH) load_kgroup(gi + 2);
           if (gi == GPH) load_vgroup(1);
           sched_fence();
         }
-        // ---- boundary: reference check of half 1 (rarely moves; then P_0 is rescaled too) ----
-        {
-          const float mx = half_max(1);
-          if (__any(mx > m_run + 8.0f)) {
-            const float m_new = fmaxf(m_run, mx);
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-            m_run = m_new;
-            l_run *= alpha;
-            rs *= alpha;
+        if (__any(!(rs0 <= 256.0f))) {  // also true for inf / NaN
+          renorm(0);
+          rs0 = 0.f;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) t[i] *= alpha;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-              for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
-          }
+          for (int i = 0; i < 16; ++i) exp_elem(i, rs0);
         }
+        load_half(1);
         v8 pf[4];
         if (DROP) drop_half(0);
         pf[0] = pack8<T>(&t[0]);
@@ -283,13 +277,19 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? (D == 64 && !CAUSAL && !DROP ? 4
           for (int dt = 0; dt < DT; ++dt) {
             o[dt] = F::mfma(vf[kk & 1][dt], pf[kk], o[dt]);
 #pragma unroll
-            for (int x = 0; x < EPV; ++x) exp_elem(16 + (kk * DT + dt) * EPV + x);
+            for (int x = 0; x < EPV; ++x) exp_elem(16 + (kk * DT + dt) * EPV + x, rs1);
             sched_fence();
           }
           load_vgroup(kk + 2);
           sched_fence();
         }
-        l_run += rs;
+        if (__any(!(rs1 <= 256.0f))) {  // P_0 V_0 is in the accumulators already and is rescaled with them
+          rs0 *= renorm(1);
+          rs1 = 0.f;
+#pragma unroll
+          for (int i = 16; i < 32; ++i) exp_elem(i, rs1);
+        }
+        l_run += rs0 + rs1;
         if (DROP) drop_half(1);
         pf[2] = pack8<T>(&t[16]);
         pf[3] = pack8<T>(&t[24]);
