@@ -217,10 +217,10 @@ def main():
             for N in (512, 1024, 2048, 4096, 16384):
                 for causal in (False, True):
                     ww = synth.Workload("S", 16384 // N, 2048 // d, N, d, synth.F16, causal, 1.0, 2000 + N + d)
-                    m2, k2 = time_workload(ww, max(5, args.steps // 3), 2)
+                    m2, k2 = time_workload(ww, max(5, args.steps // 3), args.warmup)
                     bwd_ms = k2["bwd_dot"] + k2["bwd_dkdv"] + k2["bwd_dq"]
                     # the paper's measurements run with a dropout rate of 0.1 (Sec. 4.1)
-                    m3, k3 = time_workload(ww, max(5, args.steps // 3), 2, dropout=(0.1, 2024, 0))
+                    m3, k3 = time_workload(ww, max(5, args.steps // 3), args.warmup, dropout=(0.1, 2024, 0))
                     sweep.append({"d": d, "N": N, "B": ww.B, "H": ww.H, "causal": causal,
                                   "fwd_tflops": ww.fwd_flops / (k2["fwd"] * 1e-3) / 1e12,
                                   "bwd_tflops": ww.bwd_flops / (bwd_ms * 1e-3) / 1e12,
