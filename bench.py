@@ -76,31 +76,30 @@ def time_workload(w, steps, warmup, dropout=None):
             spark_mha_dropout_bwd(Q, K, V, O, LSE, dO, w.scale, w.causal, *dropout, dQ=dQ, dK=dK,
                                   dV=dV, workspace=ws)
             if ev is not None:
-                ev.record(base + 4)
+                ev.record(base + 3)
 
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    # per step: event 0 before fwd, 1..4 recorded by spark_mha_bwd_marked
-    ev = HipEvents(5 * steps)
+    # per step: event 0 before fwd, 1..3 recorded by spark_mha_bwd_marked
+    ev = HipEvents(4 * steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(steps):
-        step(ev, 5 * s)
+        step(ev, 4 * s)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    k = {"fwd": 0.0, "bwd": 0.0} if dropout else {"fwd": 0.0, "bwd_dot": 0.0, "bwd_dkdv": 0.0, "bwd_dq": 0.0}
+    k = {"fwd": 0.0, "bwd": 0.0} if dropout else {"fwd": 0.0, "bwd_dq": 0.0, "bwd_dkdv": 0.0}
     for s in range(steps):
-        b = 5 * s
+        b = 4 * s
         k["fwd"] += ev.elapsed_ms(b, b + 1)
         if dropout:
-            k["bwd"] += ev.elapsed_ms(b + 1, b + 4)
+            k["bwd"] += ev.elapsed_ms(b + 1, b + 3)
             continue
-        k["bwd_dot"] += ev.elapsed_ms(b + 1, b + 2)
+        k["bwd_dq"] += ev.elapsed_ms(b + 1, b + 2)
         k["bwd_dkdv"] += ev.elapsed_ms(b + 2, b + 3)
-        k["bwd_dq"] += ev.elapsed_ms(b + 3, b + 4)
     # fwd+bwd of each step from the first to the last event of the step (GPU time on the stream)
-    per_step = sorted(ev.elapsed_ms(5 * s, 5 * s + 4) for s in range(steps))
+    per_step = sorted(ev.elapsed_ms(4 * s, 4 * s + 3) for s in range(steps))
     ev.close()
     k = {n: v / steps for n, v in k.items()}
     k["step_median"] = per_step[len(per_step) // 2]
@@ -193,7 +192,7 @@ def main():
                       w.sigma_qk ** 2, w.seed)},
         "pct_of_mfma_peak": 100.0 * value / PEAK_TFLOPS,
         "fwd_tflops": w.fwd_flops / (k["fwd"] * 1e-3) / 1e12,
-        "bwd_tflops": w.bwd_flops / ((k["bwd_dot"] + k["bwd_dkdv"] + k["bwd_dq"]) * 1e-3) / 1e12,
+        "bwd_tflops": w.bwd_flops / ((k["bwd_dq"] + k["bwd_dkdv"]) * 1e-3) / 1e12,
         "kernel_ms": {n: v for n, v in k.items() if not n.startswith("step_")},
         "ms_per_step_median": k["step_median"], "ms_per_step_min": k["step_min"],
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_TFLOPS,
@@ -208,7 +207,7 @@ def main():
             m2, k2 = time_workload(ww, max(5, args.steps // 2), args.warmup)
             others[name] = {"ms_per_step": m2, "tflops": (ww.fwd_flops + ww.bwd_flops) / (m2 * 1e-3) / 1e12,
                             "fwd_tflops": ww.fwd_flops / (k2["fwd"] * 1e-3) / 1e12,
-                            "bwd_tflops": ww.bwd_flops / ((k2["bwd_dot"] + k2["bwd_dkdv"] + k2["bwd_dq"]) * 1e-3) / 1e12,
+                            "bwd_tflops": ww.bwd_flops / ((k2["bwd_dq"] + k2["bwd_dkdv"]) * 1e-3) / 1e12,
                             "kernel_ms": {n: v for n, v in k2.items() if not n.startswith("step_")}}
         out["other_configs"] = others
     if args.sweep:
@@ -218,7 +217,7 @@ def main():
                 for causal in (False, True):
                     ww = synth.Workload("S", 16384 // N, 2048 // d, N, d, synth.F16, causal, 1.0, 2000 + N + d)
                     m2, k2 = time_workload(ww, max(5, args.steps // 3), args.warmup)
-                    bwd_ms = k2["bwd_dot"] + k2["bwd_dkdv"] + k2["bwd_dq"]
+                    bwd_ms = k2["bwd_dq"] + k2["bwd_dkdv"]
                     # the paper's measurements run with a dropout rate of 0.1 (Sec. 4.1)
                     m3, k3 = time_workload(ww, max(5, args.steps // 3), args.warmup, dropout=(0.1, 2024, 0))
                     sweep.append({"d": d, "N": N, "B": ww.B, "H": ww.H, "causal": causal,

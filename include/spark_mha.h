@@ -93,10 +93,10 @@ size_t spark_mha_bwd_workspace_bytes(int B, int H, int N, int d, spark_dtype_t d
  *   dQ, dK, dV     : out, device, [B,H,N,d] dtype, fully overwritten (no need to zero)
  *   workspace      : device scratch of at least spark_mha_bwd_workspace_bytes(...)
  *                    bytes, 16-byte aligned; contents on return are unspecified.
- * Enqueues, in order on `stream`: the D pre-pass, the dK/dV kernel (one
- * workgroup per key/value tile, accumulating dK and dV on chip as in Sec. 3.3)
- * and the dQ kernel (one workgroup per query tile; a separate deterministic pass
- * in place of the paper's atomic adds into HBM).
+ * Enqueues, in order on `stream`: the dQ kernel (one workgroup per query tile; a
+ * separate deterministic pass in place of the paper's atomic adds into HBM; it
+ * also forms D for its rows and leaves it in the workspace) and the dK/dV kernel
+ * (one workgroup per key/value tile, accumulating dK and dV on chip as in Sec. 3.3).
  */
 int spark_mha_bwd(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
                   const void* dO, void* dQ, void* dK, void* dV,
@@ -106,15 +106,15 @@ int spark_mha_bwd(const void* Q, const void* K, const void* V, const void* O, co
 
 /*
  * spark_mha_bwd with profiling marks: identical work, and additionally records the caller's
- * four HIP events (hipEvent_t handles, host array) on `stream`: events[0] before the D
- * pre-pass, events[1] after it, events[2] after the dK/dV kernel, events[3] after the dQ
- * kernel.  The caller creates, reads and destroys the events.  SPARK_ERR_NULL if any is NULL.
+ * three HIP events (hipEvent_t handles, host array) on `stream`: events[0] before the dQ
+ * kernel, events[1] after it, events[2] after the dK/dV kernel.  The caller creates, reads and
+ * destroys the events.  SPARK_ERR_NULL if any is NULL.
  */
 int spark_mha_bwd_marked(const void* Q, const void* K, const void* V, const void* O,
                          const float* LSE, const void* dO, void* dQ, void* dK, void* dV,
                          void* workspace, size_t workspace_bytes,
                          int B, int H, int N, int d, float scale, int causal,
-                         spark_dtype_t dtype, void* stream, void* const events[4]);
+                         spark_dtype_t dtype, void* stream, void* const events[3]);
 
 /*
  * Cross-attention forward: Eq. 1 with S = scale * Q K^T of shape Nq x Nk (Sec. 2.1, second

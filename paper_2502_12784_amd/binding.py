@@ -342,7 +342,7 @@ def spark_mha_bwd(Q, K, V, O, LSE, dO, scale: float, causal: bool, dQ=None, dK=N
     """dQ, dK, dV = fused attention backward on the current stream.
 
     ``events``: optional ``(HipEvents, first_index)``; then spark_mha_bwd_marked is called and
-    records 4 events starting at that index around the three kernels."""
+    records 3 events starting at that index around the two kernels (dQ, then dK/dV)."""
     import torch
     lib = load_library()
     B, H, N, d = Q.shape

@@ -1,13 +1,16 @@
-// Attention backward for gfx950 (paper Sec. 3.3, Eq. 4), three kernels on one stream:
+// Attention backward for gfx950 (paper Sec. 3.3, Eq. 4), two kernels on one stream, in this order:
 //
-//   mha_bwd_dot_kernel       : D_i = sum_k dO_ik O_ik (the paper's "dPsum"), and LSE*log2(e)
+//   mha_bwd_dq_kernel        : one workgroup per tile of 128 queries; first forms
+//                              D_i = sum_k dO_ik O_ik (the paper's "dPsum") for its rows from the
+//                              fragments it loads anyway and writes D and LSE*log2(e) to the
+//                              workspace, then loops over key tiles, recomputes P and dS and
+//                              accumulates dQ = scale * dS K.
 //   mha_bwd_dkdv_pipe_kernel : one workgroup per tile of 128 keys, loops over query tiles,
 //                              recomputes P = exp(S - LSE), accumulates dV = P^T dO and
 //                              dK = scale * dS^T Q in registers, writes them once (as in
 //                              Sec. 3.3, where each thread block owns a slice of dK and dV).
-//                              Software-pipelined inside the wave.
-//   mha_bwd_dq_kernel        : one workgroup per tile of 128 queries, loops over key tiles,
-//                              recomputes P and dS and accumulates dQ = scale * dS K.
+//                              Software-pipelined inside the wave.  Reads D and LSE*log2(e) from
+//                              the workspace.
 //
 // The paper adds every block's dQ contribution into HBM with atomic adds.  Here dQ has its
 // own pass with the forward's loop structure instead: it costs two recomputed contractions
@@ -28,39 +31,6 @@
 #include "tiles_gfx950.hpp"
 
 namespace spark {
-
-// ---------------------------------------------------------------------------------------
-// D = rowsum(dO o O), and LSE * log2(e) next to it.  One thread per 16-byte chunk of a row;
-// D/8 neighbouring lanes share a row and reduce with shuffles.  Pure streaming: reads two
-// tensors, writes 2*BH*N floats.
-// ---------------------------------------------------------------------------------------
-template <typename T, int D>
-__global__ __launch_bounds__(256) void mha_bwd_dot_kernel(const T* __restrict__ O,
-                                                         const T* __restrict__ dO,
-                                                         const float* __restrict__ LSE,
-                                                         float* __restrict__ Dout,
-                                                         float* __restrict__ LSE2out, TensorMap mo,
-                                                         TensorMap mdo, int H, int Nq, int64_t rows,
-                                                         float dscale) {
-  using v8 = typename Frag<T>::v8;
-  constexpr int CPR = D / 8;
-  const int64_t chunk = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t row = chunk / CPR;  // flat (batch, head, query) index
-  float acc = 0.f;
-  if (row < rows) {
-    const int bh = (int)(row / Nq), n = (int)(row - (int64_t)bh * Nq), c = (int)(chunk - row * CPR);
-    const v8 a = *reinterpret_cast<const v8*>(O + head_base(mo, bh, H) + (size_t)n * (size_t)mo.row + c * 8);
-    const v8 b = *reinterpret_cast<const v8*>(dO + head_base(mdo, bh, H) + (size_t)n * (size_t)mdo.row + c * 8);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) acc += (float)a[i] * (float)b[i];
-  }
-#pragma unroll
-  for (int off = CPR / 2; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
-  if (row < rows && (threadIdx.x % CPR) == 0) {
-    Dout[row] = acc * dscale;  // dscale = 1, or the keep probability under dropout (see dS there)
-    LSE2out[row] = LSE[row] * 1.4426950408889634f;  // the backward kernels exponentiate in base 2
-  }
-}
 
 // ---------------------------------------------------------------------------------------
 // dK, dV: software-pipelined.
@@ -414,9 +384,10 @@ template <int D> struct BwdQCfg {
 template <typename T, int D, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
-    const T* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Dws,
-    T* __restrict__ dQ, TensorMap mq, TensorMap mk, TensorMap mv, TensorMap mdo, TensorMap mdq, int H,
-    int Nq, int Nk, int nqt, float scale, float scale_log2, Dropout dr) {
+    const T* __restrict__ O, const T* __restrict__ dO, const float* __restrict__ LSE,
+    float* __restrict__ Dout, float* __restrict__ LSE2out, T* __restrict__ dQ, TensorMap mq, TensorMap mk,
+    TensorMap mv, TensorMap mo, TensorMap mdo, TensorMap mdq, int H, int Nq, int Nk, int nqt, float scale,
+    float scale_log2, Dropout dr) {
   using F = Frag<T>;
   using v8 = typename F::v8;
   using C = BwdQCfg<D>;
@@ -435,6 +406,7 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
 
   const T* Qh = Q + head_base(mq, head, H);
   const T* dOh = dO + head_base(mdo, head, H);
+  const T* Oh = O + head_base(mo, head, H);
   const BufView kview(K + head_base(mk, head, H), head_span_bytes<D>(mk, Nk));
   const BufView vview(V + head_base(mv, head, H), head_span_bytes<D>(mv, Nk));
   const uint32_t k_row_bytes = (uint32_t)mk.row * 2, v_row_bytes = (uint32_t)mv.row * 2;
@@ -457,14 +429,14 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
     const int qrow = q0 + c32;
     const int qrow_c = qrow < Nq ? qrow : Nq - 1;
 
-    v8 qf[KS], dof[KS];
+    v8 qf[KS], dof[KS], of[KS];  // of: the row of O, needed for D only
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       qf[ks] = *reinterpret_cast<const v8*>(Qh + (size_t)qrow_c * (size_t)mq.row + ks * 16 + g * 8);
       dof[ks] = *reinterpret_cast<const v8*>(dOh + (size_t)qrow_c * (size_t)mdo.row + ks * 16 + g * 8);
+      of[ks] = *reinterpret_cast<const v8*>(Oh + (size_t)qrow_c * (size_t)mo.row + ks * 16 + g * 8);
     }
-    float lse2 = LSE[(size_t)head * Nq + qrow_c] * 1.4426950408889634f;
-    float Dq = Dws[(size_t)head * Nq + qrow_c];
+    float lse2 = LSE[(size_t)head * Nq + qrow_c];
 
     int kv_end = Nk;
     if (CAUSAL) {
@@ -482,7 +454,22 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
       for (int r = 0; r < 16; ++r) dq[dt][r] = 0.f;
 
     fetch_tile(0, 0);
-    wait_vmem_all();  // Q / dO fragments and the row statistics are in registers before the loop
+    wait_vmem_all();  // Q / dO / O fragments and LSE are in registers before the loop
+    // D_i = sum_k dO_ik O_ik (the paper's "dPsum"): a lane holds half of its query's row, the lane
+    // 32 further on the other half.  Under dropout dS = r P o (M o dPraw - D (1-p)), so D is kept
+    // multiplied by the keep probability.  The dK/dV kernel runs after this one and reads D and
+    // LSE * log2(e) from the workspace.
+    float Dq = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) Dq = __builtin_fmaf((float)of[ks][i], (float)dof[ks][i], Dq);
+    Dq = half_pair_sum(Dq) * (DROP ? dr.keep_prob : 1.0f);
+    lse2 *= 1.4426950408889634f;
+    if (g == 0 && qrow < Nq) {
+      Dout[(size_t)head * Nq + qrow] = Dq;
+      LSE2out[(size_t)head * Nq + qrow] = lse2;
+    }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]), "+v"(dof[ks]));
     asm volatile("" : "+v"(lse2), "+v"(Dq));

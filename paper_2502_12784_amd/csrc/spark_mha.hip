@@ -139,12 +139,16 @@ int launch_bwd(const Problem& p, const void* Q, const void* K, const void* V, co
   };
 
   if (!mark(0)) return SPARK_ERR_LAUNCH;
-  {  // D = rowsum(dO o O): one wave per 64/(D/8) rows
-    constexpr int ROWS_PER_BLOCK = 256 / (D / 8);
-    const int64_t rows = (int64_t)BH * p.Nq;
-    const unsigned grid = (unsigned)((rows + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK);
-    hipLaunchKernelGGL((mha_bwd_dot_kernel<T, D>), dim3(grid), dim3(256), 0, p.st, o, dout, LSE, Dws,
-                       LSE2ws, p.mo, p.mdo, p.H, p.Nq, rows, DROP ? dr.keep_prob : 1.0f);
+  {  // dQ: one workgroup per tile of 128 queries (8-wave workgroups measured 3 % slower here).
+     // Also writes D = rowsum(dO o O) and LSE * log2(e) for the dK/dV kernel.
+    using C = BwdQCfg<D>;
+    auto kernel = mha_bwd_dq_kernel<T, D, CAUSAL, DROP>;
+    static const int attr = set_smem(kernel, C::SMEM);
+    if (attr != SPARK_OK) return attr;
+    const int nqt = (p.Nq + C::BM - 1) / C::BM;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nqt))), dim3(256), C::SMEM, p.st,
+                       q, k, v, o, dout, LSE, Dws, LSE2ws, static_cast<T*>(dQ), p.mq, p.mk, p.mv, p.mo,
+                       p.mdo, p.mdq, p.H, p.Nq, p.Nk, nqt, p.scale, p.scale * 1.4426950408889634f, dr);
     if (hipGetLastError() != hipSuccess || !mark(1)) return SPARK_ERR_LAUNCH;
   }
   {  // dK, dV: one workgroup per tile of 128 keys, software-pipelined
@@ -157,17 +161,6 @@ int launch_bwd(const Problem& p, const void* Q, const void* K, const void* V, co
                        q, k, v, dout, LSE2ws, Dws, static_cast<T*>(dK), static_cast<T*>(dV), p.mq, p.mk,
                        p.mv, p.mdo, p.mdk, p.mdv, p.H, p.Nq, p.Nk, nkt, p.scale, dr);
     if (hipGetLastError() != hipSuccess || !mark(2)) return SPARK_ERR_LAUNCH;
-  }
-  {  // dQ: one workgroup per tile of 128 queries (8-wave workgroups measured 3 % slower here)
-    using C = BwdQCfg<D>;
-    auto kernel = mha_bwd_dq_kernel<T, D, CAUSAL, DROP>;
-    static const int attr = set_smem(kernel, C::SMEM);
-    if (attr != SPARK_OK) return attr;
-    const int nqt = (p.Nq + C::BM - 1) / C::BM;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nqt))), dim3(256), C::SMEM, p.st,
-                       q, k, v, dout, LSE, Dws, static_cast<T*>(dQ), p.mq, p.mk, p.mv, p.mdo, p.mdq, p.H,
-                       p.Nq, p.Nk, nqt, p.scale, p.scale * 1.4426950408889634f, dr);
-    if (hipGetLastError() != hipSuccess || !mark(3)) return SPARK_ERR_LAUNCH;
   }
   return SPARK_OK;
 }
@@ -342,9 +335,9 @@ int spark_mha_bwd_marked(const void* Q, const void* K, const void* V, const void
                          const float* LSE, const void* dO, void* dQ, void* dK, void* dV,
                          void* workspace, size_t workspace_bytes, int B, int H, int N, int d,
                          float scale, int causal, spark_dtype_t dtype, void* stream,
-                         void* const events[4]) {
+                         void* const events[3]) {
   if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV || !workspace) return SPARK_ERR_NULL;
-  if (!events || !events[0] || !events[1] || !events[2] || !events[3]) return SPARK_ERR_NULL;
+  if (!events || !events[0] || !events[1] || !events[2]) return SPARK_ERR_NULL;
   Problem p;
   const int rc = make_problem(&p, B, H, N, N, d, scale, causal, 0, 0, 0, dtype, stream);
   if (rc != SPARK_OK) return rc;

@@ -82,7 +82,7 @@ def test_bwd_validation(lib):
     assert need == 2 * 128 * 4
     assert _bwd(lib, ws_bytes=need - 1) == E_WS
     assert _bwd(lib, fn="spark_mha_bwd_marked", extra=(None,)) == E_NULL
-    evs = (ctypes.c_void_p * 4)(1, 2, None, 4)
+    evs = (ctypes.c_void_p * 3)(1, None, 3)
     assert _bwd(lib, fn="spark_mha_bwd_marked", extra=(evs,)) == E_NULL
 
 
