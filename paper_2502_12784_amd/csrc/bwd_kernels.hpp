@@ -73,8 +73,7 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
   using C = BwdKvPipeCfg<D>;
   constexpr int KS = D / 16, DT = D / 32;
 
-  extern __shared__ __attribute__((aligned(16))) char smem_generic[];
-  SPARK_LDS char* smem = (SPARK_LDS char*)smem_generic;
+  SPARK_LDS char* const smem = lds_origin();
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, c32 = lane & 31;
@@ -393,8 +392,7 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
   using C = BwdQCfg<D>;
   constexpr int KS = D / 16, DT = D / 32;
 
-  extern __shared__ __attribute__((aligned(16))) char smem_generic[];
-  SPARK_LDS char* smem = (SPARK_LDS char*)smem_generic;
+  SPARK_LDS char* const smem = lds_origin();
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, c32 = lane & 31;
@@ -475,11 +473,15 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
     asm volatile("" : "+v"(lse2), "+v"(Dq));
     __syncthreads();
 
-    for (int j = 0; j < nt; ++j) {
+    // One iteration, compiled twice: MASKED for tiles that the diagonal or the end of the keys
+    // crosses, and without any mask arithmetic for all the others.
+    auto iteration = [&](const int j, auto masked_tag) {
+      constexpr bool MASKED = decltype(masked_tag)::value;
       const int buf = j & 1;
       if (j + 1 < nt) fetch_tile(j + 1, buf ^ 1);  // everybody left that buffer before the last barrier
       const int k0 = j * C::BN;
-      if (!CAUSAL || k0 <= q0 + 31) {
+      // wave-uniform: skip tiles entirely above the diagonal (they are among the masked ones)
+      if (!MASKED || !CAUSAL || k0 <= q0 + 31) {
         SPARK_LDS const char* kb = smem;  // + off.* (which carry the buffer bit)
         SPARK_LDS const char* vb = smem + C::TILE;
 
@@ -528,7 +530,6 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
         sched_fence();
 
         float ds[16 * MT];
-        const bool need_mask = (CAUSAL && k0 + C::BN - 1 > q0) || (k0 + C::BN > Nk);
         // Dropout: dS = r P o (M o dPraw - D (1-p)); the workspace holds D (1-p) and the factor r
         // goes into the final scale of dQ.
 #pragma unroll
@@ -538,7 +539,7 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mt][r], scale_log2, -lse2));
-            if (need_mask) {
+            if (MASKED) {
               const int key = k0 + mt * 32 + 8 * (r / 4) + 4 * g + (r % 4);
               const bool ok = key < Nk && (!CAUSAL || key <= qrow);
               if (!ok) pe = 0.f;
@@ -569,7 +570,16 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
         for (int dt = 0; dt < DT; ++dt) off.tr[h][dt] ^= C::STAGE;
       wait_vmem_all();  // the next tile has landed (requested at the top of the iteration)
       __syncthreads();
-    }
+    };
+    // Tiles [0, n_plain) end within the keys and, if causal, at or below the diagonal for every
+    // row of this wave.  The split differs between the waves of a workgroup; the number of
+    // iterations, and with it the number of barriers, does not.
+    int n_plain = Nk / C::BN;
+    if (CAUSAL && (q0 + 1) / C::BN < n_plain) n_plain = (q0 + 1) / C::BN;
+    if (n_plain > nt) n_plain = nt;
+    int j = 0;
+    for (; j < n_plain; ++j) iteration(j, std::false_type{});
+    for (; j < nt; ++j) iteration(j, std::true_type{});
 
     SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
     store_transposed<T, D, C::OSTR>(dq, DROP ? scale * dr.rescale : scale, ob, dQ + head_base(mdq, head, H), q0,

@@ -61,8 +61,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void mha_fwd_kernel(
   constexpr int DT = D / 32;   // 32-row tiles of O^T
   constexpr int CPR = D / 8;   // 16-byte chunks per row
 
-  extern __shared__ __attribute__((aligned(16))) char smem_generic[];
-  SPARK_LDS char* smem = (SPARK_LDS char*)smem_generic;
+  SPARK_LDS char* const smem = lds_origin();
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, c32 = lane & 31;
@@ -133,12 +132,17 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void mha_fwd_kernel(
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]));
     __syncthreads();
 
-    for (int j = 0; j < nt; ++j) {
+    // One iteration, compiled twice: MASKED for tiles that the diagonal or the end of the keys
+    // crosses, and without any mask arithmetic for all the others (left to a run-time flag, the
+    // compiler evaluates the mask predicate for every score of every tile).
+    auto iteration = [&](const int j, auto masked_tag) {
+      constexpr bool MASKED = decltype(masked_tag)::value;
       const int buf = j & 1;
       if (j + 1 < nt) fetch_tile(j + 1, buf ^ 1);  // everybody left that buffer before the last barrier
 
       const int k0 = j * C::BN;
-      if (!CAUSAL || k0 <= q0 + 31) {  // wave-uniform: skip tiles entirely above the diagonal
+      // wave-uniform: skip tiles entirely above the diagonal (they are among the masked ones)
+      if (!MASKED || !CAUSAL || k0 <= q0 + 31) {
         SPARK_LDS const char* kb = smem;  // + off.* (which carry the buffer bit)
         SPARK_LDS const char* vb = smem + C::TILE;
 
@@ -172,13 +176,12 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void mha_fwd_kernel(
             vf[kk & 1][dt] = read_tr_pair<T>(vb, off.tr[0][dt] + o, off.tr[1][dt] + o);
         };
 
-        const bool need_mask = (CAUSAL && k0 + C::BN - 1 > q0) || (k0 + C::BN > Nk);
         float t[32];
         // raw scores of one half -> t, masked
         auto load_half = [&](int h) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) t[h * 16 + r] = s[h][r];
-          if (need_mask) {
+          if (MASKED) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
               const int key = k0 + h * 32 + 8 * (r / 4) + 4 * g + (r % 4);
@@ -311,7 +314,16 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void mha_fwd_kernel(
         for (int dt = 0; dt < DT; ++dt) off.tr[h][dt] ^= C::STAGE;
       wait_vmem_all();  // the next tile has landed (requested at the top of the iteration)
       __syncthreads();
-    }
+    };
+    // Tiles [0, n_plain) end within the keys and, if causal, at or below the diagonal for every
+    // row of this wave.  The split differs between the waves of a workgroup; the number of
+    // iterations, and with it the number of barriers, does not.
+    int n_plain = Nk / C::BN;
+    if (CAUSAL && (q0 + 1) / C::BN < n_plain) n_plain = (q0 + 1) / C::BN;
+    if (n_plain > nt) n_plain = nt;
+    int j = 0;
+    for (; j < n_plain; ++j) iteration(j, std::false_type{});
+    for (; j < nt; ++j) iteration(j, std::true_type{});
 
     // Epilogue: normalise, round once, transpose through this wave's LDS slice, store rows.
     l_run = half_pair_sum(l_run);

@@ -20,6 +20,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace spark {
 
@@ -52,6 +53,15 @@ template <> struct Frag<__bf16> {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
   }
 };
+
+// Start of the workgroup's LDS as a compile-time constant.  These kernels use dynamically sized LDS
+// only, so their segment starts at LDS address 0 (the host refuses to launch a kernel whose code
+// object reports static LDS).  With a symbolic origin the compiler adds the origin to every read
+// address in the loops (one VALU instruction per LDS read); with a constant one the tile, sub-tile
+// and k-step displacements all go into the immediate field of the DS instruction.
+static __device__ __forceinline__ SPARK_LDS char* lds_origin() {
+  return reinterpret_cast<SPARK_LDS char*>(0u);
+}
 
 // 16-byte LDS read / typed LDS write at a byte offset from the start of the workgroup's LDS.
 template <typename V8>

@@ -83,6 +83,10 @@ Dropout make_dropout(int thr, unsigned long long seed, unsigned offset) {
 
 template <typename KernelT>
 int set_smem(KernelT kernel, int bytes) {
+  // The kernels address LDS from 0 (lds_origin): that holds only without static LDS in front.
+  hipFuncAttributes fa;
+  if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kernel)) != hipSuccess || fa.sharedSizeBytes != 0)
+    return SPARK_ERR_LAUNCH;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
   return e == hipSuccess ? SPARK_OK : SPARK_ERR_LAUNCH;
