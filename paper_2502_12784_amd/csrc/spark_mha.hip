@@ -94,11 +94,14 @@ int set_smem(KernelT kernel, int bytes) {
 
 // Workgroups of 8 waves (256 query rows, one per CU) instead of 4 (128 rows, two per CU): each
 // K/V tile brought into LDS then serves twice as many MFMAs.  Pays at d = 128 when the wider
-// tiles still give every CU at least two workgroups (measured -4 %; at d = 64 it costs 2 %).
+// tiles still give every CU at least two workgroups and the loop over the keys is long enough
+// to outweigh running one workgroup per CU with nothing to overlap its prologue and epilogue
+// (measured on the grid of Sec. 4.1, hidden size 2048: -5 ... -7 % from 2048 keys on, +7 ... +10 %
+// at 512, equal at 1024; at d = 64 it costs 2 %).
 template <bool CAUSAL>
 bool wide_workgroups(const Problem& p) {
   const int64_t tiles = (p.Nq + 255) / 256;
-  return p.d == 128 && (int64_t)p.B * p.H * causal_items<CAUSAL>((int)tiles) >= 512;
+  return p.d == 128 && p.Nk >= 2048 && (int64_t)p.B * p.H * causal_items<CAUSAL>((int)tiles) >= 512;
 }
 
 template <typename T, int D, bool CAUSAL, bool DROP, int NW>
