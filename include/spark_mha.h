@@ -22,9 +22,12 @@
  *     element type `dtype` (IEEE fp16 or bfloat16).  LSE has shape [B, H, N],
  *     fp32.  Pointers must be 16-byte aligned.  Inputs and outputs must not
  *     alias each other.
- *   - Supported: d in {64, 128}; any N >= 1; B, H >= 1; scale finite and > 0; causal is
- *     a flag (0 = all keys, nonzero = masked).  Size limits: B*H*ceil(N/64) < 2^31 and
- *     (N + 256)*d < 2^31.  Anything else returns SPARK_ERR_SHAPE; nothing is silently mis-computed.
+ *   - Supported: d a multiple of 8 with 8 <= d <= 128 (the paper's own sizes are 64 and 128,
+ *     Sec. 4.1; the kernels are built for rows of 64 and of 128 elements, and a smaller d runs in
+ *     the next wider one with the missing columns read as zeros, so d = 96 costs what d = 128
+ *     costs); any N >= 1; B, H >= 1; scale finite and > 0; causal is a flag (0 = all keys,
+ *     nonzero = masked).  Size limits: B*H*ceil(N/64) < 2^31 and (N + 256)*d*2 < 2^31.  Anything
+ *     else returns SPARK_ERR_SHAPE; nothing is silently mis-computed.
  *   - causal != 0: query i attends to keys j <= i (Sec. 2.1, masked MHA).
  *   - The spark_mha_cross_* entry points take Nq query rows and Nk key/value rows (Sec. 2.1:
  *     the decoder's second attention layer attends to the encoder output, so S of Eq. 1 is
@@ -59,7 +62,7 @@ typedef enum {
   SPARK_ERR_NULL = -1,      /* a required pointer is NULL */
   SPARK_ERR_SHAPE = -2,     /* B, H or N < 1; d not 64/128; a size limit exceeded; scale not
                                finite or <= 0; causal with Nq != Nk; invalid p_drop; row stride < d or
-                               a head spanning 4 GiB or more */
+                               a head spanning 2 GiB or more */
   SPARK_ERR_DTYPE = -3,     /* dtype is neither SPARK_F16 nor SPARK_BF16 */
   SPARK_ERR_ALIGN = -4,     /* a pointer, or a stride in bytes, is not a multiple of 16 */
   SPARK_ERR_WORKSPACE = -5, /* workspace too small (see spark_mha_bwd_workspace_bytes) */
@@ -190,7 +193,7 @@ int spark_dropout_mask(unsigned char* M, int B, int H, int Nq, int Nk, float p_d
  * for the batch, head and row (sequence) indices; the d elements of a row stay contiguous.  A
  * projection output laid out [B,N,H,d] is {N*H*d, d, H*d}; the contiguous default of the other
  * entry points is {H*N*d, N*d, d}.  Requirements per tensor: row >= d; batch, head >= 0; all
- * three multiples of 8 elements (16 bytes), else SPARK_ERR_ALIGN; (N + 256) * row * 2 < 2^32 bytes
+ * three multiples of 8 elements (16 bytes), else SPARK_ERR_ALIGN; (N + 256) * row * 2 < 2^31 bytes
  * (one head is addressed with 32-bit offsets), else SPARK_ERR_SHAPE; a NULL strides pointer is SPARK_ERR_NULL.  Output tensors must
  * not overlap themselves or anything else (not checked).  LSE and the workspace are always
  * contiguous [B,H,Nq].  Cross-attention (Nq, Nk) and dropout (p_drop, seed, offset; p_drop = 0

@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ dO, const float* __restrict__ LSE2, const float* __restrict__ Dws,
     T* __restrict__ dK, T* __restrict__ dV, TensorMap mq, TensorMap mk, TensorMap mv, TensorMap mdo,
-    TensorMap mdk, TensorMap mdv, int H, int Nq, int Nk, int nkt, float scale, Dropout dr) {
+    TensorMap mdk, TensorMap mdv, int H, int Nq, int Nk, int dh, int nkt, float scale, Dropout dr) {
   using F = Frag<T>;
   using v8 = typename F::v8;
   using C = BwdKvPipeCfg<D>;
@@ -85,12 +85,12 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
 
   const T* Kh = K + head_base(mk, head, H);
   const T* Vh = V + head_base(mv, head, H);
-  const BufView qview(Q + head_base(mq, head, H), head_span_bytes<D>(mq, Nq));
-  const BufView doview(dO + head_base(mdo, head, H), head_span_bytes<D>(mdo, Nq));
+  const BufView qview(Q + head_base(mq, head, H), head_span_bytes(mq, Nq, dh));
+  const BufView doview(dO + head_base(mdo, head, H), head_span_bytes(mdo, Nq, dh));
   const uint32_t q_row_bytes = (uint32_t)mq.row * 2, do_row_bytes = (uint32_t)mdo.row * 2;
   const BufView lview(LSE2 + (size_t)head * Nq, (uint32_t)Nq * 4), dview(Dws + (size_t)head * Nq, (uint32_t)Nq * 4);
-  const uint32_t q_lane_src = dma_lane_src<D>(wave, lane, q_row_bytes);
-  const uint32_t do_lane_src = dma_lane_src<D>(wave, lane, do_row_bytes);
+  const uint32_t q_lane_src = dma_lane_src<D>(wave, lane, q_row_bytes, dh);
+  const uint32_t do_lane_src = dma_lane_src<D>(wave, lane, do_row_bytes, dh);
   const float scale_log2 = scale * 1.4426950408889634f;
 
   for (int rep = 0; rep < (CAUSAL ? 2 : 1); ++rep) {
@@ -106,8 +106,8 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
     v8 kf[KS], vf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      kf[ks] = *reinterpret_cast<const v8*>(Kh + (size_t)krow_c * (size_t)mk.row + ks * 16 + g * 8);
-      vf[ks] = *reinterpret_cast<const v8*>(Vh + (size_t)krow_c * (size_t)mv.row + ks * 16 + g * 8);
+      kf[ks] = load_row_chunk<v8>(Kh + (size_t)krow_c * (size_t)mk.row, ks * 16 + g * 8, dh);
+      vf[ks] = load_row_chunk<v8>(Vh + (size_t)krow_c * (size_t)mv.row, ks * 16 + g * 8, dh);
     }
 
     f32x16 dk[DT], dv[DT];
@@ -358,9 +358,9 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
 
     SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
     store_transposed<T, D, C::OSTR>(dk, DROP ? scale * dr.rescale : scale, ob, dK + head_base(mdk, head, H), k0w,
-                                    Nk, lane, (size_t)mdk.row);
+                                    Nk, lane, (size_t)mdk.row, dh);
     store_transposed<T, D, C::OSTR>(dv, DROP ? dr.rescale : 1.0f, ob, dV + head_base(mdv, head, H), k0w, Nk,
-                                    lane, (size_t)mdv.row);
+                                    lane, (size_t)mdv.row, dh);
   }  // rep
 }
 
@@ -385,7 +385,7 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const T* __restrict__ O, const T* __restrict__ dO, const float* __restrict__ LSE,
     float* __restrict__ Dout, float* __restrict__ LSE2out, T* __restrict__ dQ, TensorMap mq, TensorMap mk,
-    TensorMap mv, TensorMap mo, TensorMap mdo, TensorMap mdq, int H, int Nq, int Nk, int nqt, float scale,
+    TensorMap mv, TensorMap mo, TensorMap mdo, TensorMap mdq, int H, int Nq, int Nk, int dh, int nqt, float scale,
     float scale_log2, Dropout dr) {
   using F = Frag<T>;
   using v8 = typename F::v8;
@@ -405,11 +405,11 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
   const T* Qh = Q + head_base(mq, head, H);
   const T* dOh = dO + head_base(mdo, head, H);
   const T* Oh = O + head_base(mo, head, H);
-  const BufView kview(K + head_base(mk, head, H), head_span_bytes<D>(mk, Nk));
-  const BufView vview(V + head_base(mv, head, H), head_span_bytes<D>(mv, Nk));
+  const BufView kview(K + head_base(mk, head, H), head_span_bytes(mk, Nk, dh));
+  const BufView vview(V + head_base(mv, head, H), head_span_bytes(mv, Nk, dh));
   const uint32_t k_row_bytes = (uint32_t)mk.row * 2, v_row_bytes = (uint32_t)mv.row * 2;
-  const uint32_t k_lane_src = dma_lane_src<D>(wave, lane, k_row_bytes);
-  const uint32_t v_lane_src = dma_lane_src<D>(wave, lane, v_row_bytes);
+  const uint32_t k_lane_src = dma_lane_src<D>(wave, lane, k_row_bytes, dh);
+  const uint32_t v_lane_src = dma_lane_src<D>(wave, lane, v_row_bytes, dh);
   // K / V tiles go global -> LDS directly (no staging registers, no LDS store instructions);
   // completion is awaited with wait_vmem_all + barrier at the end of the iteration before use.
   auto fetch_tile = [&](int j, int buf) {
@@ -430,9 +430,9 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
     v8 qf[KS], dof[KS], of[KS];  // of: the row of O, needed for D only
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      qf[ks] = *reinterpret_cast<const v8*>(Qh + (size_t)qrow_c * (size_t)mq.row + ks * 16 + g * 8);
-      dof[ks] = *reinterpret_cast<const v8*>(dOh + (size_t)qrow_c * (size_t)mdo.row + ks * 16 + g * 8);
-      of[ks] = *reinterpret_cast<const v8*>(Oh + (size_t)qrow_c * (size_t)mo.row + ks * 16 + g * 8);
+      qf[ks] = load_row_chunk<v8>(Qh + (size_t)qrow_c * (size_t)mq.row, ks * 16 + g * 8, dh);
+      dof[ks] = load_row_chunk<v8>(dOh + (size_t)qrow_c * (size_t)mdo.row, ks * 16 + g * 8, dh);
+      of[ks] = load_row_chunk<v8>(Oh + (size_t)qrow_c * (size_t)mo.row, ks * 16 + g * 8, dh);
     }
     float lse2 = LSE[(size_t)head * Nq + qrow_c];
 
@@ -583,7 +583,7 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
 
     SPARK_LDS char* ob = smem + wave * 32 * C::OSTR;
     store_transposed<T, D, C::OSTR>(dq, DROP ? scale * dr.rescale : scale, ob, dQ + head_base(mdq, head, H), q0,
-                                    Nq, lane, (size_t)mdq.row);
+                                    Nq, lane, (size_t)mdq.row, dh);
   }  // rep
 }
 

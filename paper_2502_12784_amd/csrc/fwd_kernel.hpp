@@ -52,7 +52,7 @@ template <typename T, int D, bool CAUSAL, bool DROP, int NW = 4>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void mha_fwd_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     T* __restrict__ O, float* __restrict__ LSE, TensorMap mq, TensorMap mk, TensorMap mv,
-    TensorMap mo, int H, int Nq, int Nk, int nqt, float scale_log2, Dropout dr) {
+    TensorMap mo, int H, int Nq, int Nk, int dh, int nqt, float scale_log2, Dropout dr) {
   using F = Frag<T>;
   using v8 = typename F::v8;
   using v4 = typename F::v4;
@@ -66,8 +66,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void mha_fwd_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, c32 = lane & 31;
   const uint32_t k_row_bytes = (uint32_t)mk.row * 2, v_row_bytes = (uint32_t)mv.row * 2;
-  const uint32_t k_lane_src = dma_lane_src<D>(wave & 3, lane, k_row_bytes);
-  const uint32_t v_lane_src = dma_lane_src<D>(wave & 3, lane, v_row_bytes);
+  const uint32_t k_lane_src = dma_lane_src<D>(wave & 3, lane, k_row_bytes, dh);
+  const uint32_t v_lane_src = dma_lane_src<D>(wave & 3, lane, v_row_bytes, dh);
 
   // Work items.  Non-causal: one query tile per workgroup.  Causal: a workgroup takes the pair
   // of tiles (nqt-1-p, p), whose loop lengths add up to the same total for every p, so that
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void mha_fwd_kernel(
     v8 qf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
-      qf[ks] = *reinterpret_cast<const v8*>(Qh + (size_t)qrow_c * (size_t)mq.row + ks * 16 + g * 8);
+      qf[ks] = load_row_chunk<v8>(Qh + (size_t)qrow_c * (size_t)mq.row, ks * 16 + g * 8, dh);
 
     int kv_end = Nk;
     if (CAUSAL) {
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void mha_fwd_kernel(
     const int nt = (kv_end + C::BN - 1) / C::BN;
 
     // K / V tiles: global -> LDS directly; rows past the end of the sequence arrive as zeros.
-    const BufView kview(Kh, head_span_bytes<D>(mk, Nk)), vview(Vh, head_span_bytes<D>(mv, Nk));
+    const BufView kview(Kh, head_span_bytes(mk, Nk, dh)), vview(Vh, head_span_bytes(mv, Nk, dh));
     auto fetch_tile = [&](int j, int buf) {  // four waves move a tile
       if (NW > 4 && wave >= 4) return;
       tile_dma<D, C::BN>(kview, j * C::BN, smem + buf * C::STAGE, wave, k_lane_src, k_row_bytes);
@@ -344,7 +344,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void mha_fwd_kernel(
     for (int p = 0; p < 32 / RPP; ++p) {
       const int row = p * RPP + lane / CPR, cc = lane % CPR;
       const u32x4 v = lds_read16<u32x4>(ob, row * C::OSTR + cc * 16);
-      if (q0 + row < Nq) *reinterpret_cast<u32x4*>(Oh + (size_t)(q0 + row) * (size_t)mo.row + cc * 8) = v;
+      if (q0 + row < Nq && cc * 8 < dh)
+        *reinterpret_cast<u32x4*>(Oh + (size_t)(q0 + row) * (size_t)mo.row + cc * 8) = v;
     }
     if (g == 0 && qrow < Nq)
       LSE[(size_t)head * Nq + qrow] = (m_run + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f;

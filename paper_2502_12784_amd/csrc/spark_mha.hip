@@ -38,14 +38,14 @@ int check_common(int B, int H, int Nq, int Nk, int d, float scale, int causal, i
   if (dtype != SPARK_F16 && dtype != SPARK_BF16) return SPARK_ERR_DTYPE;
   if (B < 1 || H < 1 || Nq < 1 || Nk < 1) return SPARK_ERR_SHAPE;
   if (causal && Nq != Nk) return SPARK_ERR_SHAPE;  // the mask is defined for a square S only
-  if (d != 64 && d != 128) return SPARK_ERR_SHAPE;
+  if (d < 8 || d > 128 || (d & 7)) return SPARK_ERR_SHAPE;  // rows of 16-byte chunks, tiles up to 128 wide
   if (!isfinite(scale) || !(scale > 0.f)) return SPARK_ERR_SHAPE;
   const int64_t bh = (int64_t)B * H;
   const int64_t nmax = Nq > Nk ? Nq : Nk;
   const int64_t tiles64 = (nmax + 63) / 64;
   if (bh * tiles64 >= (int64_t)1 << 31) return SPARK_ERR_SHAPE;
-  // 32-bit byte offsets inside one head, including the rows a ragged last tile reaches past N
-  if ((nmax + 256) * d >= (int64_t)1 << 31) return SPARK_ERR_SHAPE;
+  // 31-bit byte offsets inside one head, including the rows a ragged last tile reaches past N
+  if ((nmax + 256) * d * 2 >= (int64_t)1 << 31) return SPARK_ERR_SHAPE;
   return SPARK_OK;
 }
 
@@ -56,8 +56,9 @@ int check_strides(const spark_strides_t* s, int N, int d, TensorMap* out) {
   if (!s) return SPARK_ERR_NULL;
   if (s->batch < 0 || s->head < 0 || s->row < d) return SPARK_ERR_SHAPE;
   if ((s->batch | s->head | s->row) & 7) return SPARK_ERR_ALIGN;
-  // 32-bit byte offsets inside one head, including the rows a ragged last tile reaches past N
-  if ((int64_t)(N + 256) * s->row * 2 >= (int64_t)1 << 32) return SPARK_ERR_SHAPE;
+  // 31-bit byte offsets inside one head, including the rows a ragged last tile reaches past N
+  // (offsets from 2^31 on are how the kernels mark chunks that must read as zeros)
+  if ((int64_t)(N + 256) * s->row * 2 >= (int64_t)1 << 31) return SPARK_ERR_SHAPE;
   *out = TensorMap{s->batch, s->head, s->row};
   return SPARK_OK;
 }
@@ -101,7 +102,7 @@ int set_smem(KernelT kernel, int bytes) {
 template <bool CAUSAL>
 bool wide_workgroups(const Problem& p) {
   const int64_t tiles = (p.Nq + 255) / 256;
-  return p.d == 128 && p.Nk >= 2048 && (int64_t)p.B * p.H * causal_items<CAUSAL>((int)tiles) >= 512;
+  return p.d > 64 && p.Nk >= 2048 && (int64_t)p.B * p.H * causal_items<CAUSAL>((int)tiles) >= 512;
 }
 
 template <typename T, int D, bool CAUSAL, bool DROP, int NW>
@@ -115,7 +116,7 @@ int launch_fwd_nw(const Problem& p, const void* Q, const void* K, const void* V,
   const float scale_log2 = p.scale * 1.4426950408889634f;
   hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nqt))), dim3(64 * NW), C::SMEM, p.st,
                      static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
-                     static_cast<T*>(O), LSE, p.mq, p.mk, p.mv, p.mo, p.H, p.Nq, p.Nk, nqt, scale_log2,
+                     static_cast<T*>(O), LSE, p.mq, p.mk, p.mv, p.mo, p.H, p.Nq, p.Nk, p.d, nqt, scale_log2,
                      make_dropout(p.thr, p.seed, p.offset));
   return hipGetLastError() == hipSuccess ? SPARK_OK : SPARK_ERR_LAUNCH;
 }
@@ -155,7 +156,7 @@ int launch_bwd(const Problem& p, const void* Q, const void* K, const void* V, co
     const int nqt = (p.Nq + C::BM - 1) / C::BM;
     hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nqt))), dim3(256), C::SMEM, p.st,
                        q, k, v, o, dout, LSE, Dws, LSE2ws, static_cast<T*>(dQ), p.mq, p.mk, p.mv, p.mo,
-                       p.mdo, p.mdq, p.H, p.Nq, p.Nk, nqt, p.scale, p.scale * 1.4426950408889634f, dr);
+                       p.mdo, p.mdq, p.H, p.Nq, p.Nk, p.d, nqt, p.scale, p.scale * 1.4426950408889634f, dr);
     if (hipGetLastError() != hipSuccess || !mark(1)) return SPARK_ERR_LAUNCH;
   }
   {  // dK, dV: one workgroup per tile of 128 keys, software-pipelined
@@ -166,7 +167,7 @@ int launch_bwd(const Problem& p, const void* Q, const void* K, const void* V, co
     const int nkt = (p.Nk + C::BN - 1) / C::BN;
     hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nkt))), dim3(256), C::SMEM, p.st,
                        q, k, v, dout, LSE2ws, Dws, static_cast<T*>(dK), static_cast<T*>(dV), p.mq, p.mk,
-                       p.mv, p.mdo, p.mdk, p.mdv, p.H, p.Nq, p.Nk, nkt, p.scale, dr);
+                       p.mv, p.mdo, p.mdk, p.mdv, p.H, p.Nq, p.Nk, p.d, nkt, p.scale, dr);
     if (hipGetLastError() != hipSuccess || !mark(2)) return SPARK_ERR_LAUNCH;
   }
   return SPARK_OK;
@@ -182,10 +183,10 @@ int launch_bwd(const Problem& p, const void* Q, const void* K, const void* V, co
 #define SPARK_DISPATCH(FN, ...)                                              \
   do {                                                                       \
     if (p.dtype == SPARK_F16) {                                              \
-      if (p.d == 64) SPARK_DISPATCH_CD(FN, _Float16, 64, __VA_ARGS__);       \
+      if (p.d <= 64) SPARK_DISPATCH_CD(FN, _Float16, 64, __VA_ARGS__);       \
       SPARK_DISPATCH_CD(FN, _Float16, 128, __VA_ARGS__);                     \
     }                                                                        \
-    if (p.d == 64) SPARK_DISPATCH_CD(FN, __bf16, 64, __VA_ARGS__);           \
+    if (p.d <= 64) SPARK_DISPATCH_CD(FN, __bf16, 64, __VA_ARGS__);           \
     SPARK_DISPATCH_CD(FN, __bf16, 128, __VA_ARGS__);                         \
   } while (0)
 

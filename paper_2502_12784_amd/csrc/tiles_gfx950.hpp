@@ -26,10 +26,21 @@ static __device__ __forceinline__ size_t head_base(const TensorMap& m, int bh, i
   const int b = bh / H, h = bh - b * H;
   return (size_t)b * (size_t)m.batch + (size_t)h * (size_t)m.head;
 }
-// Bytes a buffer view of one head must span: rows 0..n-1, the last one d elements long.
-template <int D>
-static __device__ __forceinline__ uint32_t head_span_bytes(const TensorMap& m, int n) {
-  return (uint32_t)(((size_t)(n - 1) * (size_t)m.row + D) * 2);
+// Bytes a buffer view of one head must span: rows 0..n-1, the last one dh elements long.
+static __device__ __forceinline__ uint32_t head_span_bytes(const TensorMap& m, int n, int dh) {
+  return (uint32_t)(((size_t)(n - 1) * (size_t)m.row + (size_t)dh) * 2);
+}
+
+// Head dimensions below the tile width.  The kernels are compiled for rows of D = 64 or 128
+// elements; a head dimension dh < D (a multiple of 8) runs in the next wider one with the columns
+// dh..D-1 of every operand read as zeros (they add nothing to any contraction) and never stored.
+// A fragment load of 8 elements starting at column `col`:
+template <typename V8, typename T>
+static __device__ __forceinline__ V8 load_row_chunk(const T* row, int col, int dh) {
+  V8 z;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) z[i] = (T)0.f;
+  return col < dh ? *reinterpret_cast<const V8*>(row + col) : z;
 }
 
 // Work items per head for a kernel that walks `tiles` tiles: causal kernels pair tile p with
@@ -98,13 +109,16 @@ static __device__ __forceinline__ typename Frag<T>::v8 read_tr_pair(SPARK_LDS co
 // blocks w, w+4, ... of the tile; lane l writes bytes [16 l, 16 l + 16) of its block, so it
 // fetches the logical chunk that the swizzle places there.  `lane_src` is that per-lane source
 // offset for block `wave` (the later blocks are a multiple of 16 rows further on, where the
-// swizzle repeats).  Rows past the end of the matrix arrive as zeros.  `row_bytes` is the
-// distance between consecutive rows in global memory (2*D when the rows are contiguous).
+// swizzle repeats).  Rows past the end of the matrix arrive as zeros, and so do the chunks at
+// columns >= dh: their lanes get a source offset of 2^31, which no tile offset (< 2^31, the host
+// checks it) brings back inside the view.  `row_bytes` is the distance between consecutive rows
+// in global memory (2*dh when the rows are contiguous).
 template <int D>
-static __device__ __forceinline__ uint32_t dma_lane_src(int wave, int lane, uint32_t row_bytes) {
+static __device__ __forceinline__ uint32_t dma_lane_src(int wave, int lane, uint32_t row_bytes, int dh) {
   const int byte = wave * 1024 + lane * 16;
   const int row = byte / (2 * D), pc = (byte % (2 * D)) >> 4;
-  return (uint32_t)row * row_bytes + (uint32_t)((pc ^ swz<D>(row)) << 4);
+  const int chunk = pc ^ swz<D>(row);
+  return chunk * 8 < dh ? (uint32_t)row * row_bytes + (uint32_t)(chunk << 4) : 0x80000000u;
 }
 template <int D, int ROWS>
 static __device__ __forceinline__ void tile_dma(const BufView& view, int r0, SPARK_LDS char* dst,
@@ -118,11 +132,11 @@ static __device__ __forceinline__ void tile_dma(const BufView& view, int r0, SPA
 
 // Write a wave's transposed accumulator (D x 32, lane = column) times `mul` as 32 rows of D
 // 16-bit values: through the wave's LDS slice `ob`, then 16-byte row stores for rows < N
-// (`row_stride` elements apart).
+// and columns < dh (`row_stride` elements apart).
 template <typename T, int D, int OSTR>
 static __device__ __forceinline__ void store_transposed(const f32x16 (&acc)[D / 32], float mul,
                                                         SPARK_LDS char* ob, T* __restrict__ out,
-                                                        int row0, int N, int lane, size_t row_stride) {
+                                                        int row0, int N, int lane, size_t row_stride, int dh) {
   using v4 = typename Frag<T>::v4;
   constexpr int CPR = D / 8;
   constexpr int RPP = 64 / CPR;
@@ -140,7 +154,8 @@ static __device__ __forceinline__ void store_transposed(const f32x16 (&acc)[D / 
   for (int p = 0; p < 32 / RPP; ++p) {
     const int row = p * RPP + lane / CPR, cc = lane % CPR;
     const u32x4 v = lds_read16<u32x4>(ob, row * OSTR + cc * 16);
-    if (row0 + row < N) *reinterpret_cast<u32x4*>(out + (size_t)(row0 + row) * row_stride + cc * 8) = v;
+    if (row0 + row < N && cc * 8 < dh)
+      *reinterpret_cast<u32x4*>(out + (size_t)(row0 + row) * row_stride + cc * 8) = v;
   }
 }
 

@@ -53,8 +53,8 @@ def test_fwd_validation_has_no_side_effects(lib):
     assert _fwd(lib, lse=None) == E_NULL
     assert _fwd(lib, B=0) == E_SHAPE
     assert _fwd(lib, N=0) == E_SHAPE
-    assert _fwd(lib, d=96) == E_SHAPE
-    assert _fwd(lib, d=32) == E_SHAPE
+    assert _fwd(lib, d=100) == E_SHAPE
+    assert _fwd(lib, d=136) == E_SHAPE
     assert _fwd(lib, scale=0.0) == E_SHAPE
     assert _fwd(lib, scale=-1.0) == E_SHAPE
     assert _fwd(lib, scale=float("nan")) == E_SHAPE
@@ -62,7 +62,9 @@ def test_fwd_validation_has_no_side_effects(lib):
     assert _fwd(lib, dtype=2) == E_DTYPE
     assert _fwd(lib, k=0x2008) == E_ALIGN
     assert _fwd(lib, B=1 << 20, H=1 << 10, N=1 << 12) == E_SHAPE  # grid would overflow
-    assert _fwd(lib, N=1 << 25, d=128) == E_SHAPE                 # N*d >= 2^31
+    assert _fwd(lib, N=1 << 25, d=128) == E_SHAPE                 # a head of 2 GiB or more
+    for bad_d in (0, 4, 100, 136, 256):                           # multiples of 8 up to 128 only
+        assert _fwd(lib, d=bad_d) == E_SHAPE
 
 
 def _bwd(lib, fn="spark_mha_bwd", ws=0xA000, ws_bytes=1 << 20, dq=0x7000, B=1, H=1, N=128, d=64,
@@ -81,6 +83,8 @@ def test_bwd_validation(lib):
     need = pkg.spark_mha_bwd_workspace_bytes(1, 1, 128, 64, 0)
     assert need == 2 * 128 * 4
     assert _bwd(lib, ws_bytes=need - 1) == E_WS
+    assert _bwd(lib, d=96, ws_bytes=need - 1) == E_WS  # d = 96 passes the shape checks
+    assert _bwd(lib, d=8, ws_bytes=need - 1) == E_WS
     assert _bwd(lib, fn="spark_mha_bwd_marked", extra=(None,)) == E_NULL
     evs = (ctypes.c_void_p * 3)(1, None, 3)
     assert _bwd(lib, fn="spark_mha_bwd_marked", extra=(evs,)) == E_NULL
@@ -154,7 +158,7 @@ def test_strided_validation(lib):
     assert fwd(sq=S(-8, 0, 64)) == E_SHAPE
     assert fwd(sk=S(0, 0, 68)) == E_ALIGN              # 136-byte rows
     assert fwd(so=S(4, 0, 64)) == E_ALIGN
-    assert fwd(sq=S(0, 0, 1 << 24), N=1024) == E_SHAPE  # one head would span 4 GiB or more
+    assert fwd(sq=S(0, 0, 1 << 24), N=1024) == E_SHAPE  # one head would span 2 GiB or more
     eight = [S(128 * 64, 64 * 128, 64)] * 8
     args = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000, 0x8000, 0x9000]
     tail = [0xA000, 1 << 20, 1, 1, 128, 128, 64, 0.125, 0, 0.0, 0, 0, 0, None]

@@ -105,7 +105,7 @@ def test_errors_leave_outputs_untouched():
     LSE = torch.full((B, H, N), 7.0, dtype=torch.float32, device="cuda")
     st = torch.cuda.current_stream().cuda_stream
     args = [dev["Q"].data_ptr(), dev["K"].data_ptr(), dev["V"].data_ptr(), O.data_ptr(), LSE.data_ptr()]
-    assert lib.spark_mha_fwd(*args, B, H, N, 96, 0.125, 0, 0, st) == -2        # head dim
+    assert lib.spark_mha_fwd(*args, B, H, N, 100, 0.125, 0, 0, st) == -2        # head dim
     assert lib.spark_mha_fwd(*args, B, H, N, d, -0.125, 0, 0, st) == -2       # scale
     assert lib.spark_mha_fwd(*args, B, H, N, d, 0.125, 0, 5, st) == -3        # dtype
     assert lib.spark_mha_fwd(args[0] + 2, *args[1:], B, H, N, d, 0.125, 0, 0, st) == -4  # alignment

@@ -16,7 +16,8 @@ pytestmark = pytest.mark.gpu
 
 def _draw(seed):
     r = np.random.default_rng(seed)
-    d = int(r.choice([64, 128]))
+    # the paper's two head sizes for the first 40 seeds, any supported one afterwards
+    d = int(r.choice([64, 128])) if seed < 3040 else 8 * int(r.integers(1, 17))
     dtype = [synth.F16, synth.BF16][int(r.integers(2))]
     causal = bool(r.integers(2))
     B, H = int(r.integers(1, 4)), int(r.integers(1, 5))
@@ -41,7 +42,7 @@ def _lay_out(t, layout):
     return v
 
 
-@pytest.mark.parametrize("seed", list(range(3000, 3040)))
+@pytest.mark.parametrize("seed", list(range(3000, 3064)))
 def test_random_problem(seed):
     import torch
     from paper_2502_12784_amd import spark_dropout_threshold, spark_mha_strided_bwd, spark_mha_strided_fwd
