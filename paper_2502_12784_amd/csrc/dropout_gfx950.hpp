@@ -56,6 +56,27 @@ static __device__ __forceinline__ uint32_t quad_bcast(uint32_t v) {
   return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, A * 0x55, 0xF, 0xF, true);
 }
 
+// 4 x 4 transpose inside every quad: on return x[a] holds what lane a of the quad had in x[w],
+// w = this lane's position in the quad.  Two butterfly steps (partner lane w^1, then w^2), each
+// exchanging the two words that differ in that bit: 4 DPP moves and 12 selects.
+static __device__ __forceinline__ void quad_transpose(uint32_t (&x)[4], int w) {
+  const bool odd = w & 1, upper = w & 2;
+#pragma unroll
+  for (int k = 0; k < 4; k += 2) {  // words k, k+1 <-> lane bit 0
+    const uint32_t send = odd ? x[k] : x[k + 1];
+    const uint32_t recv = (uint32_t)__builtin_amdgcn_mov_dpp((int)send, 0xB1, 0xF, 0xF, true);  // quad_perm [1,0,3,2]
+    x[k] = odd ? recv : x[k];
+    x[k + 1] = odd ? x[k + 1] : recv;
+  }
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {  // words k, k+2 <-> lane bit 1
+    const uint32_t send = upper ? x[k] : x[k + 2];
+    const uint32_t recv = (uint32_t)__builtin_amdgcn_mov_dpp((int)send, 0x4E, 0xF, 0xF, true);  // quad_perm [2,3,0,1]
+    x[k] = upper ? recv : x[k];
+    x[k + 2] = upper ? x[k + 2] : recv;
+  }
+}
+
 // Lane = query column (S^T layouts of the forward and dQ kernels).  The lane's query is
 // `qrow` (qrow mod 4 == lane mod 4) and it holds keys kblk + 8a + 4g + b of the 32-key block
 // starting at kblk (a multiple of 32), g = lane / 32.  kb[a] receives the four decision bytes of
@@ -66,13 +87,10 @@ static __device__ __forceinline__ void keep_bytes_query_lane(const Dropout& dr, 
   uint32_t x[4];
   philox4x32_10((uint32_t)((kblk >> 2) + 2 * w + g), (uint32_t)(qrow >> 2), (uint32_t)head, dr.offset,
                 dr.key0, dr.key1, x);  // this lane evaluates the call of strip a = w
-  auto own_row = [&](uint32_t x0, uint32_t x1, uint32_t x2, uint32_t x3) {
-    return w == 0 ? x0 : w == 1 ? x1 : w == 2 ? x2 : x3;  // word (query mod 4) of the call
-  };
-  kb[0] = own_row(quad_bcast<0>(x[0]), quad_bcast<0>(x[1]), quad_bcast<0>(x[2]), quad_bcast<0>(x[3]));
-  kb[1] = own_row(quad_bcast<1>(x[0]), quad_bcast<1>(x[1]), quad_bcast<1>(x[2]), quad_bcast<1>(x[3]));
-  kb[2] = own_row(quad_bcast<2>(x[0]), quad_bcast<2>(x[1]), quad_bcast<2>(x[2]), quad_bcast<2>(x[3]));
-  kb[3] = own_row(quad_bcast<3>(x[0]), quad_bcast<3>(x[1]), quad_bcast<3>(x[2]), quad_bcast<3>(x[3]));
+  // strip a needs word (query mod 4) = w of the call that lane a of the quad evaluated
+  quad_transpose(x, w);
+#pragma unroll
+  for (int a = 0; a < 4; ++a) kb[a] = x[a];
 }
 
 // Lane = key column (S layouts of the dK/dV kernel).  The lane's key is `krow`
