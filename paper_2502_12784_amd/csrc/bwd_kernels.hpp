@@ -194,6 +194,7 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
       if (DROP) {
         const bool keep = keep_reg(kb, r, dr.thr);
         p[r8] = keep ? pe : 0.f;
+        asm volatile("" : "+v"(p[r8]));  // keeps the select in front of the packed conversion
         ds[r8] = pe * ((keep ? dp[r] : 0.f) - d[r8 >> 2][r8 & 3]);
       } else {
         p[r8] = pe;

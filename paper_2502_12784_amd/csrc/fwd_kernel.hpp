@@ -221,8 +221,12 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void mha_fwd_kernel(
           uint32_t kb[4];
           keep_bytes_query_lane(dr, head, qrow, k0 + 32 * h, lane, kb);
 #pragma unroll
-          for (int r = 0; r < 16; ++r)
+          for (int r = 0; r < 16; ++r) {
             if (!keep_reg(kb, r, dr.thr)) t[h * 16 + r] = 0.f;
+            // the select stays on the fp32 value: moved behind the conversion it would split every
+            // packed two-value conversion into single ones plus a merge
+            asm volatile("" : "+v"(t[h * 16 + r]));
+          }
         };
         float rs0 = 0.f, rs1 = 0.f;  // this lane's sums of P over the two halves
         auto exp_elem = [&](int i, float& rs) {
