@@ -230,6 +230,15 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
       if (gi + 2 < NG) load_agroup(gi + 2, 0);
       sched_fence();
     }
+    // At D = 128 every step requests the first two fragment groups of its successor half-way through
+    // its own dV / dK region, so that no step starts by waiting for LDS (C4 backward -3 %); here
+    // those of step (s_begin, 1).  At D = 64 the longer live ranges cost spills (+1 ... +3 %) and the
+    // request stays at the start of the step that uses it.
+    constexpr bool EARLY = D == 128;
+    if (EARLY) {
+      load_agroup(0, 1);
+      load_agroup(1, 1);
+    }
     // The MFMAs deliver the scores in accumulation registers, which the VALU cannot use as
     // operands, and a copy out of them stalls while any MFMA is executing (measured: reading them
     // element by element between MFMAs serialises the two pipes completely).  So each finished
@@ -261,7 +270,8 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
 
       // One step.  cur: scores complete, first half of P / dS packed.  new: the step after it
       // (sub_new inside the stage rowA / statA point at).
-      auto step = [&](f32x16& s_new, f32x16& dp_new, int sub_new, int q0_new, int sub_cur, int q0_cur) {
+      auto step = [&](f32x16& s_new, f32x16& dp_new, int sub_new, int q0_new, int sub_cur, int q0_cur,
+                      auto&& request_next) {
         // ---- region 1: scores of the next step  ||  second half of P, dS of the current step ----
         float p[8], ds[8];
         // dropout decisions of the next step: the ten generator rounds ride in the MFMA slots below
@@ -310,6 +320,7 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
             sched_fence();
           }
           if (tg + 2 < NTG) load_tgroup(tg + 2, sub_cur);
+          if (EARLY && tg == NTG / 2 - 1) request_next();  // the fragment buffers are free since region 1 ended
           sched_fence();
         }
         pfL = pack8<T>(p);
@@ -326,18 +337,24 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
       // (m, 1) scores  ||  (m, 0) softmax; then (m, 0) dV / dK
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sY[r] = 0.f; dpY[r] = 0.f; }
-      load_agroup(0, 1);
-      load_agroup(1, 1);
+      auto request_B = [&] {
+        point_A(slot1);  // stage m+1 has been resident since the end of stage m-1
+        load_agroup(0, 0);
+        load_agroup(1, 0);
+      };
+      auto request_A = [&] {
+        load_agroup(0, 1);
+        load_agroup(1, 1);
+      };
+      if (!EARLY) request_A();
       sched_fence();
-      step(sY, dpY, 1, m * C::BM + 32, 0, m * C::BM);
+      step(sY, dpY, 1, m * C::BM + 32, 0, m * C::BM, request_B);
       // (m+1, 0) scores  ||  (m, 1) softmax; then (m, 1) dV / dK
-      point_A(slot1);
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sX[r] = 0.f; dpX[r] = 0.f; }
-      load_agroup(0, 0);
-      load_agroup(1, 0);
+      if (!EARLY) request_B();
       sched_fence();
-      step(sX, dpX, 0, (m + 1) * C::BM, 1, m * C::BM + 32);
+      step(sX, dpX, 0, (m + 1) * C::BM, 1, m * C::BM + 32, request_A);
 
       point_C(slot1);
       wait_vmem_all();  // stage m+2 has landed (it was requested a whole stage ago)
