@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused MHA hot path on one MI355X.
 
-One step = spark_mha_fwd followed by spark_mha_bwd (D pre-pass, dK/dV kernel, dQ kernel) on
+One step = spark_mha_fwd followed by spark_mha_bwd (dQ kernel, which also forms D = rowsum(dO o O); dK/dV kernel) on
 one synthetic batch that is already resident in HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--all] [--no-cpu]
