@@ -200,6 +200,10 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
         p[r8] = pe;
         ds[r8] = pe * (dp[r] - d[r8 >> 2][r8 & 3]);
       }
+      // materialise dS here, between the MFMAs around this call: it is not used before the packing
+      // at the end of the region, and the compiler would otherwise move its arithmetic there,
+      // where no MFMA hides it
+      asm volatile("" : "+v"(ds[r8]));
     };
     uint32_t kbCur[4] = {0, 0, 0, 0}, kbNew[4] = {0, 0, 0, 0};  // decision bytes of the current / next step
 
@@ -239,13 +243,11 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
       load_agroup(0, 1);
       load_agroup(1, 1);
     }
-    // The MFMAs deliver the scores in accumulation registers, which the VALU cannot use as
-    // operands, and a copy out of them stalls while any MFMA is executing (measured: reading them
-    // element by element between MFMAs serialises the two pipes completely).  So each finished
-    // score tile is copied to VALU registers in one burst, right after the region that formed it,
-    // and all softmax arithmetic works on the copies sV / dpV.
-    f32x16 sV = sX, dpV = dpX;
-    asm volatile("" : "+v"(sV), "+v"(dpV));
+    // With more than 256 registers per lane the MFMAs deliver the scores in accumulation registers,
+    // which the VALU reaches through one v_accvgpr_read per element.  Such a read co-issues with
+    // executing MFMAs as long as none of them writes the register read (measured), so each element
+    // is read where its softmax arithmetic sits, between the MFMAs of the following regions; the
+    // two score buffers X / Y alternate so that the one being read is never the one being formed.
     // P / dS operands of the current step: registers 0..7 (pfL, dsfL) are formed one region
     // early, registers 8..15 (pfH, dsfH) while the next step's scores are on the matrix cores.
     v8 pfL, dsfL;
@@ -253,7 +255,7 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
       float p[8], ds[8];
       if (DROP) keep_bytes_key_lane(dr, head, krow, s_begin * C::BM, lane, kbCur);
 #pragma unroll
-      for (int r = 0; r < 8; ++r) softmax_elem(sV, dpV, 0, r, lL, dL, s_begin * C::BM, CAUSAL, kbCur, p, ds);
+      for (int r = 0; r < 8; ++r) softmax_elem(sX, dpX, 0, r, lL, dL, s_begin * C::BM, CAUSAL, kbCur, p, ds);
       pfL = pack8<T>(p);
       dsfL = pack8<T>(ds);
     }
@@ -270,8 +272,8 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
 
       // One step.  cur: scores complete, first half of P / dS packed.  new: the step after it
       // (sub_new inside the stage rowA / statA point at).
-      auto step = [&](f32x16& s_new, f32x16& dp_new, int sub_new, int q0_new, int sub_cur, int q0_cur,
-                      auto&& request_next) {
+      auto step = [&](f32x16& s_new, f32x16& dp_new, int sub_new, int q0_new, const f32x16& s_cur,
+                      const f32x16& dp_cur, int sub_cur, int q0_cur, auto&& request_next) {
         // ---- region 1: scores of the next step  ||  second half of P, dS of the current step ----
         float p[8], ds[8];
         // dropout decisions of the next step: the ten generator rounds ride in the MFMA slots below
@@ -290,7 +292,7 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
           if (i == 2 * NG) load_tgroup(1, sub_cur);
           if (i & 1) {
 #pragma unroll
-            for (int x = 0; x < E1; ++x) softmax_elem(sV, dpV, 1, (i / 2) * E1 + x, lH, dH, q0_cur, mask, kbCur, p, ds);
+            for (int x = 0; x < E1; ++x) softmax_elem(s_cur, dp_cur, 1, (i / 2) * E1 + x, lH, dH, q0_cur, mask, kbCur, p, ds);
           }
           if (DROP) {
 #pragma unroll
@@ -303,9 +305,6 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
         const v8 pfH = pack8<T>(p), dsfH = pack8<T>(ds);
         load_stats(lH, dH, sub_new, 1);
         sched_fence();
-        sV = s_new;  // burst copy of the scores just formed (see above)
-        dpV = dp_new;
-        asm volatile("" : "+v"(sV), "+v"(dpV));
         sched_fence();
         // ---- region 2: dV, dK of the current step  ||  first half of P, dS of the next step ----
 #pragma unroll
@@ -315,8 +314,8 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
           for (int e = 0; e < 2; ++e) {
             dv[dt0 + e] = F::mfma(ft[tg & 1][2 * e], kk ? pfH : pfL, dv[dt0 + e]);
             dk[dt0 + e] = F::mfma(ft[tg & 1][2 * e + 1], kk ? dsfH : dsfL, dk[dt0 + e]);
-            softmax_elem(sV, dpV, 0, (8 / NTG) * tg + e, lL, dL, q0_new, mask, kbNew, p, ds);
-            if (8 / NTG > 2) softmax_elem(sV, dpV, 0, (8 / NTG) * tg + 2 + e, lL, dL, q0_new, mask, kbNew, p, ds);
+            softmax_elem(s_new, dp_new, 0, (8 / NTG) * tg + e, lL, dL, q0_new, mask, kbNew, p, ds);
+            if (8 / NTG > 2) softmax_elem(s_new, dp_new, 0, (8 / NTG) * tg + 2 + e, lL, dL, q0_new, mask, kbNew, p, ds);
             sched_fence();
           }
           if (tg + 2 < NTG) load_tgroup(tg + 2, sub_cur);
@@ -348,13 +347,13 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
       };
       if (!EARLY) request_A();
       sched_fence();
-      step(sY, dpY, 1, m * C::BM + 32, 0, m * C::BM, request_B);
+      step(sY, dpY, 1, m * C::BM + 32, sX, dpX, 0, m * C::BM, request_B);
       // (m+1, 0) scores  ||  (m, 1) softmax; then (m, 1) dV / dK
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sX[r] = 0.f; dpX[r] = 0.f; }
       if (!EARLY) request_B();
       sched_fence();
-      step(sX, dpX, 0, (m + 1) * C::BM, 1, m * C::BM + 32, request_A);
+      step(sX, dpX, 0, (m + 1) * C::BM, sY, dpY, 1, m * C::BM + 32, request_A);
 
       point_C(slot1);
       wait_vmem_all();  // stage m+2 has landed (it was requested a whole stage ago)
