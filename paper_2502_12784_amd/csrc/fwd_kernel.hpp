@@ -232,6 +232,9 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void mha_fwd_kernel(
         auto exp_elem = [&](int i, float& rs) {
           t[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(t[i], scale_log2, -m_run));
           rs += t[i];
+          // materialise here, between the MFMAs around this call: nothing uses the values before the
+          // end of the phase, and the compiler otherwise moves the arithmetic there
+          asm volatile("" : "+v"(t[i]), "+v"(rs));
         };
 
         // ---- S_0 ----
