@@ -502,38 +502,72 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
         SPARK_LDS const char* kb = smem;  // + off.* (which carry the buffer bit)
         SPARK_LDS const char* vb = smem + C::TILE;
 
-        // S^T = K Q^T and dP^T = V dO^T (lane = query column, registers = keys); the row
-        // fragments of one k-step (MT key blocks x {K, V}) are read two steps ahead of the MFMAs.
+        // S^T = K Q^T first, then dP^T = V dO^T (lane = query column, registers = keys), so that
+        // P = exp2(S c - LSE) can be formed under the MFMAs of dP, and the second half of dS under
+        // the first MFMAs of dQ.  A wave issues in order: what overlaps is decided by program
+        // order, so the arithmetic is placed between the MFMAs by hand, pinned by empty asm
+        // statements (the compiler would move it to its first use) and scheduling fences.
+        // Row fragments (step i < KS: K at k-step i; step i >= KS: V at k-step i - KS) are read
+        // four steps ahead of their MFMAs.
         constexpr int MT = C::BN / 32;  // 32-key blocks per tile
         f32x16 s[MT], dp[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
           for (int r = 0; r < 16; ++r) { s[mt][r] = 0.f; dp[mt][r] = 0.f; }
-        v8 fa[2][2 * MT];
-        auto load_agroup = [&](int ks) {
+        constexpr int AHEAD = 4;
+        v8 fa[AHEAD][MT];
+        auto load_step = [&](int i) {
+          const int ks = i < KS ? i : i - KS;
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) {
-            const int o = off.row[ks] + mt * 32 * C::ROWB;
-            fa[ks & 1][2 * mt] = lds_read16<v8>(kb, o);
-            fa[ks & 1][2 * mt + 1] = lds_read16<v8>(vb, o);
-          }
+          for (int mt = 0; mt < MT; ++mt)
+            fa[i % AHEAD][mt] = lds_read16<v8>(i < KS ? kb : vb, off.row[ks] + mt * 32 * C::ROWB);
         };
-        load_agroup(0);
-        load_agroup(1);
+        // Dropout: dS = r P o (M o dPraw - D (1-p)); the workspace holds D (1-p) and the factor r
+        // goes into the final scale of dQ.
+        uint32_t keep[MT][4];
+        if (DROP) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) keep_bytes_query_lane(dr, head, qrow, k0 + 32 * mt, lane, keep[mt]);
+        }
+#pragma unroll
+        for (int i = 0; i < AHEAD; ++i) load_step(i);
         sched_fence();
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) {
-            s[mt] = F::mfma(fa[ks & 1][2 * mt], qf[ks], s[mt]);
-            dp[mt] = F::mfma(fa[ks & 1][2 * mt + 1], dof[ks], dp[mt]);
-          }
-          if (ks + 2 < KS) load_agroup(ks + 2);
+          for (int mt = 0; mt < MT; ++mt) s[mt] = F::mfma(fa[ks % AHEAD][mt], qf[ks], s[mt]);
+          load_step(ks + AHEAD);  // KS >= AHEAD: always a valid step
           sched_fence();
         }
 
-        // K^T fragments of the first two 16-key steps fly during the softmax arithmetic
+        float pe[16 * MT];
+        auto p_elem = [&](int e) {  // e = mt * 16 + r
+          const int mt = e / 16, r = e % 16;
+          float x = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mt][r], scale_log2, -lse2));
+          if (MASKED) {
+            const int key = k0 + mt * 32 + 8 * (r / 4) + 4 * g + (r % 4);
+            const bool ok = key < Nk && (!CAUSAL || key <= qrow);
+            if (!ok) x = 0.f;
+          }
+          pe[e] = x;
+          asm volatile("" : "+v"(pe[e]));
+        };
+        constexpr int EPM = 16 / KS;  // P elements per MFMA of dP
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            dp[mt] = F::mfma(fa[(KS + ks) % AHEAD][mt], dof[ks], dp[mt]);
+#pragma unroll
+            for (int x = 0; x < EPM; ++x) p_elem(mt * 16 + ks * EPM + x);
+            sched_fence();
+          }
+          if (KS + ks + AHEAD < 2 * KS) load_step(KS + ks + AHEAD);
+          sched_fence();
+        }
+
+        // K^T fragments of the first two 16-key steps
         constexpr int NKK = C::BN / 16;
         v8 ft[2][DT];
         auto load_tgroup = [&](int kk) {
@@ -547,34 +581,34 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
         sched_fence();
 
         float ds[16 * MT];
-        // Dropout: dS = r P o (M o dPraw - D (1-p)); the workspace holds D (1-p) and the factor r
-        // goes into the final scale of dQ.
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          uint32_t kb[4];
-          if (DROP) keep_bytes_query_lane(dr, head, qrow, k0 + 32 * mt, lane, kb);
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mt][r], scale_log2, -lse2));
-            if (MASKED) {
-              const int key = k0 + mt * 32 + 8 * (r / 4) + 4 * g + (r % 4);
-              const bool ok = key < Nk && (!CAUSAL || key <= qrow);
-              if (!ok) pe = 0.f;
-            }
-            const float dpe = DROP && !keep_reg(kb, r, dr.thr) ? 0.f : dp[mt][r];
-            ds[mt * 16 + r] = pe * (dpe - Dq);
-          }
-        }
+        auto ds_elem = [&](int e) {
+          const int mt = e / 16, r = e % 16;
+          const float dpe = DROP && !keep_reg(keep[mt], r, dr.thr) ? 0.f : dp[mt][r];
+          ds[e] = pe[e] * (dpe - Dq);
+          asm volatile("" : "+v"(ds[e]));
+        };
+        // dQ^T += K^T dS^T, 16 keys per step; step kk uses elements 8 kk .. 8 kk + 7.  Those of
+        // step 0 are formed up front, those of step kk + 1 under the MFMAs of step kk.
         v8 dsf[NKK];
 #pragma unroll
-        for (int kk = 0; kk < NKK; ++kk) dsf[kk] = pack8<T>(&ds[kk * 8]);
+        for (int x = 0; x < 8; ++x) ds_elem(x);
+        dsf[0] = pack8<T>(&ds[0]);
         sched_fence();
-
-        // dQ^T += K^T dS^T, 16 keys per step
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) {
 #pragma unroll
-          for (int dt = 0; dt < DT; ++dt) dq[dt] = F::mfma(ft[kk & 1][dt], dsf[kk], dq[dt]);
+          for (int dt = 0; dt < DT; ++dt) {
+            dq[dt] = F::mfma(ft[kk & 1][dt], dsf[kk], dq[dt]);
+            if (kk + 1 < NKK) {
+#pragma unroll
+              for (int x = 0; x < 8 / DT; ++x) ds_elem(8 * (kk + 1) + dt * (8 / DT) + x);
+            }
+            sched_fence();
+          }
+          if (kk + 1 < NKK) {
+            dsf[kk + 1] = pack8<T>(&ds[8 * (kk + 1)]);
+            asm volatile("" : "+v"(dsf[kk + 1]));
+          }
           if (kk + 2 < NKK) load_tgroup(kk + 2);
           sched_fence();
         }
