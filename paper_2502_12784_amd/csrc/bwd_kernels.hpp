@@ -187,7 +187,7 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
     // dS = r P o (M o dPraw - D (1-p)): the workspace holds D (1-p), r goes into the final scales.
     auto softmax_elem = [&](const f32x16& s, const f32x16& dp, int half, int r8, const f32x4 (&l)[2],
                             const f32x4 (&d)[2], int q0s, bool mask, const uint32_t (&kb)[4], float* p,
-                            float* ds) {
+                            float* ds, uint32_t (&pk_p)[4], uint32_t (&pk_ds)[4]) {
       const int r = 8 * half + r8;
       float pe = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, -l[r8 >> 2][r8 & 3]));
       if (mask) pe = krow > q0s + 8 * (r / 4) + 4 * g + (r % 4) ? 0.f : pe;
@@ -204,6 +204,10 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
       // at the end of the region, and the compiler would otherwise move its arithmetic there,
       // where no MFMA hides it
       asm volatile("" : "+v"(ds[r8]));
+      if (r8 & 1) {  // a pair is complete: convert it now
+        pk_p[r8 >> 1] = pack2<T>(p[r8 - 1], p[r8]);
+        pk_ds[r8 >> 1] = pack2<T>(ds[r8 - 1], ds[r8]);
+      }
     };
     uint32_t kbCur[4] = {0, 0, 0, 0}, kbNew[4] = {0, 0, 0, 0};  // decision bytes of the current / next step
 
@@ -253,11 +257,13 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
     v8 pfL, dsfL;
     {
       float p[8], ds[8];
+      uint32_t pk_p[4], pk_ds[4];
       if (DROP) keep_bytes_key_lane(dr, head, krow, s_begin * C::BM, lane, kbCur);
 #pragma unroll
-      for (int r = 0; r < 8; ++r) softmax_elem(sX, dpX, 0, r, lL, dL, s_begin * C::BM, CAUSAL, kbCur, p, ds);
-      pfL = pack8<T>(p);
-      dsfL = pack8<T>(ds);
+      for (int r = 0; r < 8; ++r)
+        softmax_elem(sX, dpX, 0, r, lL, dL, s_begin * C::BM, CAUSAL, kbCur, p, ds, pk_p, pk_ds);
+      pfL = join_pairs<T>(pk_p);
+      dsfL = join_pairs<T>(pk_ds);
     }
     load_stats(lH, dH, 0, 1);
 
@@ -276,6 +282,7 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
                       const f32x16& dp_cur, int sub_cur, int q0_cur, auto&& request_next) {
         // ---- region 1: scores of the next step  ||  second half of P, dS of the current step ----
         float p[8], ds[8];
+        uint32_t pk_p[4], pk_ds[4];
         // dropout decisions of the next step: the ten generator rounds ride in the MFMA slots below
         Philox rng;
         if (DROP) rng = keep_key_lane_begin(dr, head, krow, q0_new, lane);
@@ -292,7 +299,7 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
           if (i == 2 * NG) load_tgroup(1, sub_cur);
           if (i & 1) {
 #pragma unroll
-            for (int x = 0; x < E1; ++x) softmax_elem(s_cur, dp_cur, 1, (i / 2) * E1 + x, lH, dH, q0_cur, mask, kbCur, p, ds);
+            for (int x = 0; x < E1; ++x) softmax_elem(s_cur, dp_cur, 1, (i / 2) * E1 + x, lH, dH, q0_cur, mask, kbCur, p, ds, pk_p, pk_ds);
           }
           if (DROP) {
 #pragma unroll
@@ -302,7 +309,7 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
           sched_fence();
         }
         if (DROP) keep_key_lane_finish(rng, lane, kbNew);
-        const v8 pfH = pack8<T>(p), dsfH = pack8<T>(ds);
+        const v8 pfH = join_pairs<T>(pk_p), dsfH = join_pairs<T>(pk_ds);
         load_stats(lH, dH, sub_new, 1);
         sched_fence();
         sched_fence();
@@ -314,16 +321,17 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
           for (int e = 0; e < 2; ++e) {
             dv[dt0 + e] = F::mfma(ft[tg & 1][2 * e], kk ? pfH : pfL, dv[dt0 + e]);
             dk[dt0 + e] = F::mfma(ft[tg & 1][2 * e + 1], kk ? dsfH : dsfL, dk[dt0 + e]);
-            softmax_elem(s_new, dp_new, 0, (8 / NTG) * tg + e, lL, dL, q0_new, mask, kbNew, p, ds);
-            if (8 / NTG > 2) softmax_elem(s_new, dp_new, 0, (8 / NTG) * tg + 2 + e, lL, dL, q0_new, mask, kbNew, p, ds);
+            softmax_elem(s_new, dp_new, 0, (8 / NTG) * tg + e, lL, dL, q0_new, mask, kbNew, p, ds, pk_p, pk_ds);
+            if (8 / NTG > 2)
+              softmax_elem(s_new, dp_new, 0, (8 / NTG) * tg + 2 + e, lL, dL, q0_new, mask, kbNew, p, ds, pk_p, pk_ds);
             sched_fence();
           }
           if (tg + 2 < NTG) load_tgroup(tg + 2, sub_cur);
           if (EARLY && tg == NTG / 2 - 1) request_next();  // the fragment buffers are free since region 1 ended
           sched_fence();
         }
-        pfL = pack8<T>(p);
-        dsfL = pack8<T>(ds);
+        pfL = join_pairs<T>(pk_p);
+        dsfL = join_pairs<T>(pk_ds);
         // materialise here: otherwise this arithmetic sinks to its use in the next step and
         // runs there with no MFMA to hide it
         asm volatile("" : "+v"(pfL), "+v"(dsfL));

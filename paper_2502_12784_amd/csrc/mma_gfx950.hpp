@@ -95,6 +95,25 @@ static __device__ __forceinline__ typename Frag<T>::v8 pack8(const float* x) {
   return r;
 }
 
+// Two fp32 values to one register of two 16-bit values (one packed conversion), and four such
+// registers as one MFMA operand: for kernels that convert each pair as soon as it exists, between
+// MFMAs, instead of all eight values at the end of a phase.
+template <typename T>
+static __device__ __forceinline__ uint32_t pack2(float a, float b) {
+  typedef T v2 __attribute__((ext_vector_type(2)));
+  v2 r;
+  r[0] = (T)a;
+  r[1] = (T)b;
+  uint32_t u = __builtin_bit_cast(uint32_t, r);
+  asm volatile("" : "+v"(u));
+  return u;
+}
+template <typename T>
+static __device__ __forceinline__ typename Frag<T>::v8 join_pairs(const uint32_t (&u)[4]) {
+  const u32x4 v = {u[0], u[1], u[2], u[3]};
+  return __builtin_bit_cast(typename Frag<T>::v8, v);
+}
+
 // Reductions over the two lanes l and l^32 (the two halves of a wave), result in both lanes.
 // v_permlane32_swap exchanges the upper half of its first operand with the lower half of its
 // second; called with (x, x) it returns {x of the lower-half lane, x of the upper-half lane} in
