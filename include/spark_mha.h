@@ -18,6 +18,8 @@
  *   - All tensor pointers are DEVICE pointers owned by the caller.  The library
  *     never allocates, frees or synchronises; it only enqueues kernels on
  *     `stream` (a hipStream_t passed as void*; NULL means the default stream).
+ *     The work runs on the calling thread's current device, which must be the device that
+ *     `stream` and all pointers belong to; each device is set up on its first call.
  *   - Q, K, V, O, dO, dQ, dK, dV have shape [B, H, N, d], contiguous, d fastest,
  *     element type `dtype` (IEEE fp16 or bfloat16).  LSE has shape [B, H, N],
  *     fp32.  Pointers must be 16-byte aligned.  Inputs and outputs must not

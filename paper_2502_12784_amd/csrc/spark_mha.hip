@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
+#include <atomic>
 
 #include "bwd_kernels.hpp"
 #include "fwd_kernel.hpp"
@@ -93,6 +94,19 @@ int set_smem(KernelT kernel, int bytes) {
   return e == hipSuccess ? SPARK_OK : SPARK_ERR_LAUNCH;
 }
 
+// set_smem once per kernel and device: the attribute belongs to the function on the current
+// device, so a process that drives several GPUs needs it on each of them.  `done` holds one bit
+// per device ordinal; a failure is not remembered, the next call tries again.
+template <typename KernelT>
+int ensure_smem(KernelT kernel, int bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0) return SPARK_ERR_LAUNCH;
+  if (dev < 64 && ((done.load(std::memory_order_acquire) >> dev) & 1u)) return SPARK_OK;
+  const int rc = set_smem(kernel, bytes);
+  if (rc == SPARK_OK && dev < 64) done.fetch_or(uint64_t(1) << dev, std::memory_order_release);
+  return rc;
+}
+
 // Workgroups of 8 waves (256 query rows, one per CU) instead of 4 (128 rows, two per CU): each
 // K/V tile brought into LDS then serves twice as many MFMAs.  Pays at d = 128 when the wider
 // tiles still give every CU at least two workgroups and the loop over the keys is long enough
@@ -109,7 +123,8 @@ template <typename T, int D, bool CAUSAL, bool DROP, int NW>
 int launch_fwd_nw(const Problem& p, const void* Q, const void* K, const void* V, void* O, float* LSE) {
   using C = FwdCfg<D, NW>;
   auto kernel = mha_fwd_kernel<T, D, CAUSAL, DROP, NW>;
-  static const int attr = set_smem(kernel, C::SMEM);
+  static std::atomic<uint64_t> ready{0};
+  const int attr = ensure_smem(kernel, C::SMEM, ready);
   if (attr != SPARK_OK) return attr;
   const int BH = p.B * p.H;
   const int nqt = (p.Nq + C::BM - 1) / C::BM;
@@ -151,7 +166,8 @@ int launch_bwd(const Problem& p, const void* Q, const void* K, const void* V, co
      // Also writes D = rowsum(dO o O) and LSE * log2(e) for the dK/dV kernel.
     using C = BwdQCfg<D>;
     auto kernel = mha_bwd_dq_kernel<T, D, CAUSAL, DROP>;
-    static const int attr = set_smem(kernel, C::SMEM);
+    static std::atomic<uint64_t> ready{0};
+    const int attr = ensure_smem(kernel, C::SMEM, ready);
     if (attr != SPARK_OK) return attr;
     const int nqt = (p.Nq + C::BM - 1) / C::BM;
     hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nqt))), dim3(256), C::SMEM, p.st,
@@ -162,7 +178,8 @@ int launch_bwd(const Problem& p, const void* Q, const void* K, const void* V, co
   {  // dK, dV: one workgroup per tile of 128 keys, software-pipelined
     using C = BwdKvPipeCfg<D>;
     auto kernel = mha_bwd_dkdv_pipe_kernel<T, D, CAUSAL, DROP>;
-    static const int attr = set_smem(kernel, C::SMEM);
+    static std::atomic<uint64_t> ready{0};
+    const int attr = ensure_smem(kernel, C::SMEM, ready);
     if (attr != SPARK_OK) return attr;
     const int nkt = (p.Nk + C::BN - 1) / C::BN;
     hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nkt))), dim3(256), C::SMEM, p.st,
