@@ -327,7 +327,10 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
             sched_fence();
           }
           if (tg + 2 < NTG) load_tgroup(tg + 2, sub_cur);
-          if (EARLY && tg == NTG / 2 - 1) request_next();  // the fragment buffers are free since region 1 ended
+          // the fragment buffers are free since region 1 ended; one group per slot keeps the number
+          // of LDS reads in flight under the 15 the wave's counter can track
+          if (EARLY && tg == NTG / 2 - 1) request_next(0);
+          if (EARLY && tg == NTG / 2) request_next(1);
           sched_fence();
         }
         pfL = join_pairs<T>(pk_p);
@@ -344,22 +347,22 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
       // (m, 1) scores  ||  (m, 0) softmax; then (m, 0) dV / dK
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sY[r] = 0.f; dpY[r] = 0.f; }
-      auto request_B = [&] {
-        point_A(slot1);  // stage m+1 has been resident since the end of stage m-1
-        load_agroup(0, 0);
-        load_agroup(1, 0);
+      auto request_B = [&](int part) {
+        if (part != 1) point_A(slot1);  // stage m+1 has been resident since the end of stage m-1
+        if (part != 1) load_agroup(0, 0);
+        if (part != 0) load_agroup(1, 0);
       };
-      auto request_A = [&] {
-        load_agroup(0, 1);
-        load_agroup(1, 1);
+      auto request_A = [&](int part) {
+        if (part != 1) load_agroup(0, 1);
+        if (part != 0) load_agroup(1, 1);
       };
-      if (!EARLY) request_A();
+      if (!EARLY) request_A(2);
       sched_fence();
       step(sY, dpY, 1, m * C::BM + 32, sX, dpX, 0, m * C::BM, request_B);
       // (m+1, 0) scores  ||  (m, 1) softmax; then (m, 1) dV / dK
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sX[r] = 0.f; dpX[r] = 0.f; }
-      if (!EARLY) request_B();
+      if (!EARLY) request_B(2);
       sched_fence();
       step(sX, dpX, 0, (m + 1) * C::BM, sY, dpY, 1, m * C::BM + 32, request_A);
 
