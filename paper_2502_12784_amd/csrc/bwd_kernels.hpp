@@ -171,14 +171,13 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
     constexpr int NTG = 2 * (DT / 2);
     constexpr int E1 = 8 / (2 * NG);  // softmax elements per pair of score MFMAs in region 1
     v8 ft[2][4];
-    auto load_tgroup = [&](int tg, int sub) {
+    // half e of transposed-fragment group tg (one dO^T and one Q^T operand: four reads); issued in
+    // halves so that no MFMA slot carries more than a few LDS reads
+    auto load_thalf = [&](int tg, int sub, int e) {
       const int kk = tg / (DT / 2), dt0 = 2 * (tg % (DT / 2));
       const int o = sub * 32 * C::ROWB + kk * 16 * C::ROWB;
-#pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        ft[tg & 1][2 * e] = read_tr_pair<T>(smem + C::TILE, trC[0][dt0 + e] + o, trC[1][dt0 + e] + o);
-        ft[tg & 1][2 * e + 1] = read_tr_pair<T>(smem, trC[0][dt0 + e] + o, trC[1][dt0 + e] + o);
-      }
+      ft[tg & 1][2 * e] = read_tr_pair<T>(smem + C::TILE, trC[0][dt0 + e] + o, trC[1][dt0 + e] + o);
+      ft[tg & 1][2 * e + 1] = read_tr_pair<T>(smem, trC[0][dt0 + e] + o, trC[1][dt0 + e] + o);
     };
 
     // One element of P and dS from finished scores: the unit of VALU work that is placed between
@@ -287,7 +286,7 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
         Philox rng;
         if (DROP) rng = keep_key_lane_begin(dr, head, krow, q0_new, lane);
         load_stats(lL, dL, sub_new, 0);
-        load_tgroup(0, sub_cur);
+        load_thalf(0, sub_cur, 0);
 #pragma unroll
         for (int i = 0; i < 4 * NG; ++i) {
           const int gi = i / 4, e = (i / 2) & 1;
@@ -296,7 +295,9 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
           else
             dp_new = F::mfma(fa[gi & 1][2 * e + 1], vf[2 * gi + e], dp_new);
           if ((i & 3) == 3 && gi + 2 < NG) load_agroup(gi + 2, sub_new);
-          if (i == 2 * NG) load_tgroup(1, sub_cur);
+          if (i == 1) load_thalf(0, sub_cur, 1);
+          if (i == 2 * NG) load_thalf(1, sub_cur, 0);
+          if (i == 2 * NG + 1) load_thalf(1, sub_cur, 1);
           if (i & 1) {
 #pragma unroll
             for (int x = 0; x < E1; ++x) softmax_elem(s_cur, dp_cur, 1, (i / 2) * E1 + x, lH, dH, q0_cur, mask, kbCur, p, ds, pk_p, pk_ds);
@@ -324,9 +325,9 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
             softmax_elem(s_new, dp_new, 0, (8 / NTG) * tg + e, lL, dL, q0_new, mask, kbNew, p, ds, pk_p, pk_ds);
             if (8 / NTG > 2)
               softmax_elem(s_new, dp_new, 0, (8 / NTG) * tg + 2 + e, lL, dL, q0_new, mask, kbNew, p, ds, pk_p, pk_ds);
+            if (tg + 2 < NTG) load_thalf(tg + 2, sub_cur, e);  // into the operands just used
             sched_fence();
           }
-          if (tg + 2 < NTG) load_tgroup(tg + 2, sub_cur);
           // the fragment buffers are free since region 1 ended; one group per slot keeps the number
           // of LDS reads in flight under the 15 the wave's counter can track
           if (EARLY && tg == NTG / 2 - 1) request_next(0);
