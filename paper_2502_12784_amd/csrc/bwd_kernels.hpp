@@ -565,6 +565,17 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
           pe[e] = x;
           asm volatile("" : "+v"(pe[e]));
         };
+        // K^T fragments, one group per 16-key step of dQ; the first two groups are requested in
+        // the second half of the dP phase, when the row fragments have all been requested (one
+        // burst of all of them would exceed the 15 LDS reads a wave can have in flight)
+        constexpr int NKK = C::BN / 16;
+        v8 ft[2][DT];
+        auto load_tgroup = [&](int kk) {
+          const int o = kk * 16 * C::ROWB;
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt)
+            ft[kk & 1][dt] = read_tr_pair<T>(kb, off.tr[0][dt] + o, off.tr[1][dt] + o);
+        };
         constexpr int EPM = 16 / KS;  // P elements per MFMA of dP
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -576,21 +587,10 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
             sched_fence();
           }
           if (KS + ks + AHEAD < 2 * KS) load_step(KS + ks + AHEAD);
+          if (ks == KS - AHEAD) load_tgroup(0);
+          if (ks == KS - AHEAD / 2) load_tgroup(1);
           sched_fence();
         }
-
-        // K^T fragments of the first two 16-key steps
-        constexpr int NKK = C::BN / 16;
-        v8 ft[2][DT];
-        auto load_tgroup = [&](int kk) {
-          const int o = kk * 16 * C::ROWB;
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt)
-            ft[kk & 1][dt] = read_tr_pair<T>(kb, off.tr[0][dt] + o, off.tr[1][dt] + o);
-        };
-        load_tgroup(0);
-        load_tgroup(1);
-        sched_fence();
 
         float ds[16 * MT];
         auto ds_elem = [&](int e) {
