@@ -62,9 +62,10 @@ typedef enum { SPARK_F16 = 0, SPARK_BF16 = 1 } spark_dtype_t;
 typedef enum {
   SPARK_OK = 0,
   SPARK_ERR_NULL = -1,      /* a required pointer is NULL */
-  SPARK_ERR_SHAPE = -2,     /* B, H or N < 1; d not 64/128; a size limit exceeded; scale not
-                               finite or <= 0; causal with Nq != Nk; invalid p_drop; row stride < d or
-                               a head spanning 2 GiB or more */
+  SPARK_ERR_SHAPE = -2,     /* B, H or N < 1; d not a multiple of 8 in 8..128; a size limit exceeded;
+                               scale not finite or <= 0; causal with Nq != Nk; invalid p_drop; row
+                               stride < d, a head spanning 2 GiB or more, or an output tensor with a
+                               zero batch (B > 1) or head (H > 1) stride */
   SPARK_ERR_DTYPE = -3,     /* dtype is neither SPARK_F16 nor SPARK_BF16 */
   SPARK_ERR_ALIGN = -4,     /* a pointer, or a stride in bytes, is not a multiple of 16 */
   SPARK_ERR_WORKSPACE = -5, /* workspace too small (see spark_mha_bwd_workspace_bytes) */
@@ -196,8 +197,11 @@ int spark_dropout_mask(unsigned char* M, int B, int H, int Nq, int Nk, float p_d
  * projection output laid out [B,N,H,d] is {N*H*d, d, H*d}; the contiguous default of the other
  * entry points is {H*N*d, N*d, d}.  Requirements per tensor: row >= d; batch, head >= 0; all
  * three multiples of 8 elements (16 bytes), else SPARK_ERR_ALIGN; (N + 256) * row * 2 < 2^31 bytes
- * (one head is addressed with 32-bit offsets), else SPARK_ERR_SHAPE; a NULL strides pointer is SPARK_ERR_NULL.  Output tensors must
- * not overlap themselves or anything else (not checked).  LSE and the workspace are always
+ * (one head is addressed with 32-bit offsets), else SPARK_ERR_SHAPE; a NULL strides pointer is
+ * SPARK_ERR_NULL.  A zero batch or head stride broadcasts an INPUT over that index; for an output
+ * (O, dQ, dK, dV) it would make every (batch, head) store to the same rows and is refused with
+ * SPARK_ERR_SHAPE when B > 1 (batch) or H > 1 (head).  Other overlaps of output tensors with
+ * themselves or anything else are not checked and must not occur.  LSE and the workspace are always
  * contiguous [B,H,Nq].  Cross-attention (Nq, Nk) and dropout (p_drop, seed, offset; p_drop = 0
  * for none) as in the entry points above; same kernels, same guarantees.
  */

@@ -36,12 +36,24 @@ class SparkError(RuntimeError):
         self.status = status
 
 
+def library_is_stale() -> bool:
+    """True if the shared library is missing or older than any of the sources it is built from."""
+    if not os.path.exists(LIB_PATH):
+        return True
+    built = os.path.getmtime(LIB_PATH)
+    csrc = os.path.join(HERE, "csrc")
+    sources = [os.path.join(csrc, f) for f in os.listdir(csrc) if f.endswith((".hip", ".hpp", ".h"))]
+    sources.append(os.path.join(os.path.dirname(HERE), "include", "spark_mha.h"))
+    return any(os.path.getmtime(f) > built for f in sources if os.path.exists(f))
+
+
 def load_library() -> ctypes.CDLL:
-    """Load the in-tree shared library; build it only if it does not exist."""
+    """Load the in-tree shared library; build it first if it is missing or older than its sources
+    (an edit under csrc/ must never be tested or timed against the previous binary)."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
+    if library_is_stale():
         from .build import build_library
         build_library()
     lib = ctypes.CDLL(LIB_PATH)

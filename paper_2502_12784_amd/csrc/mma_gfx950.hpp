@@ -151,20 +151,21 @@ struct BufView {
   // which would expose the whole global-memory latency.  The caller therefore owns the
   // synchronisation: wait_vmem_all() followed by a workgroup barrier before anyone reads the
   // destination.  (The compiler's own vmcnt waits stay correct: loads return in order, so
-  // extra outstanding loads can only make such a wait longer, never shorter.)  M0 is written
-  // without telling the compiler (it rejects M0 as a clobber); nothing else in these kernels
-  // uses M0: no other LDS-DMA, GWS or relative-index instruction is generated.
+  // extra outstanding loads can only make such a wait longer, never shorter.)  The LDS
+  // destination travels in M0; it is handed over as an input operand bound to that register, so
+  // the compiler writes M0 itself and knows its value is consumed here: any use of M0 of its
+  // own (another LDS-DMA, GWS or relative-index instruction) is ordered around it correctly.
   __device__ __forceinline__ void load16_to_lds(SPARK_LDS char* dst, uint32_t lane_off, uint32_t tile_off) const {
-    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+    asm volatile("buffer_load_dwordx4 %1, %2, %3 offen lds"
                  :
-                 : "s"(__builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst)), "v"(lane_off), "s"(desc),
+                 : "{m0}"(__builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst)), "v"(lane_off), "s"(desc),
                    "s"(__builtin_amdgcn_readfirstlane(tile_off))
                  : "memory");
   }
   __device__ __forceinline__ void load4_to_lds(SPARK_LDS char* dst, uint32_t lane_off, uint32_t tile_off) const {
-    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+    asm volatile("buffer_load_dword %1, %2, %3 offen lds"
                  :
-                 : "s"(__builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst)), "v"(lane_off), "s"(desc),
+                 : "{m0}"(__builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst)), "v"(lane_off), "s"(desc),
                    "s"(__builtin_amdgcn_readfirstlane(tile_off))
                  : "memory");
   }

@@ -53,9 +53,13 @@ int check_common(int B, int H, int Nq, int Nk, int d, float scale, int causal, i
 // A strided tensor is usable if rows hold d contiguous elements, every stride keeps 16-byte
 // alignment, and one head's rows span less than 4 GiB (the kernels address a head through a
 // 32-bit buffer descriptor).
-int check_strides(const spark_strides_t* s, int N, int d, TensorMap* out) {
+// An output tensor must in addition give every (batch, head) its own rows: a zero batch or head stride
+// (a broadcast, fine for an input) would make all those workgroups store to the same memory.
+int check_strides(const spark_strides_t* s, int N, int d, TensorMap* out, bool is_output = false, int B = 1,
+                  int H = 1) {
   if (!s) return SPARK_ERR_NULL;
   if (s->batch < 0 || s->head < 0 || s->row < d) return SPARK_ERR_SHAPE;
+  if (is_output && ((B > 1 && s->batch == 0) || (H > 1 && s->head == 0))) return SPARK_ERR_SHAPE;
   if ((s->batch | s->head | s->row) & 7) return SPARK_ERR_ALIGN;
   // 31-bit byte offsets inside one head, including the rows a ragged last tile reaches past N
   // (offsets from 2^31 on are how the kernels mark chunks that must read as zeros)
@@ -288,7 +292,7 @@ int spark_mha_strided_fwd(const void* Q, const void* K, const void* V, void* O, 
   if ((rc = check_strides(sQ, Nq, d, &p.mq)) != SPARK_OK) return rc;
   if ((rc = check_strides(sK, Nk, d, &p.mk)) != SPARK_OK) return rc;
   if ((rc = check_strides(sV, Nk, d, &p.mv)) != SPARK_OK) return rc;
-  if ((rc = check_strides(sO, Nq, d, &p.mo)) != SPARK_OK) return rc;
+  if ((rc = check_strides(sO, Nq, d, &p.mo, true, B, H)) != SPARK_OK) return rc;
   return run_fwd(p, Q, K, V, O, LSE);
 }
 
@@ -350,9 +354,9 @@ int spark_mha_strided_bwd(const void* Q, const void* K, const void* V, const voi
   if ((rc = check_strides(sV, Nk, d, &p.mv)) != SPARK_OK) return rc;
   if ((rc = check_strides(sO, Nq, d, &p.mo)) != SPARK_OK) return rc;
   if ((rc = check_strides(sdO, Nq, d, &p.mdo)) != SPARK_OK) return rc;
-  if ((rc = check_strides(sdQ, Nq, d, &p.mdq)) != SPARK_OK) return rc;
-  if ((rc = check_strides(sdK, Nk, d, &p.mdk)) != SPARK_OK) return rc;
-  if ((rc = check_strides(sdV, Nk, d, &p.mdv)) != SPARK_OK) return rc;
+  if ((rc = check_strides(sdQ, Nq, d, &p.mdq, true, B, H)) != SPARK_OK) return rc;
+  if ((rc = check_strides(sdK, Nk, d, &p.mdk, true, B, H)) != SPARK_OK) return rc;
+  if ((rc = check_strides(sdV, Nk, d, &p.mdv, true, B, H)) != SPARK_OK) return rc;
   return run_bwd(p, Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, nullptr);
 }
 
@@ -391,8 +395,9 @@ const char* spark_status_str(int status) {
     case SPARK_OK: return "ok";
     case SPARK_ERR_NULL: return "a required pointer is NULL";
     case SPARK_ERR_SHAPE:
-      return "unsupported shape, scale, dropout rate or stride (need B,H,N >= 1, d in {64,128}, finite "
-             "scale > 0, Nq == Nk if causal, 0 <= p_drop < 0.998, row stride >= d)";
+      return "unsupported shape, scale, dropout rate or stride (need B,H,N >= 1, d a multiple of 8 with "
+             "8 <= d <= 128, finite scale > 0, Nq == Nk if causal, 0 <= p_drop < 0.998, row stride >= d, "
+             "nonzero batch/head strides for outputs, sizes within the documented limits)";
     case SPARK_ERR_DTYPE: return "unsupported dtype (need SPARK_F16 or SPARK_BF16)";
     case SPARK_ERR_ALIGN: return "a pointer or stride is not 16-byte aligned";
     case SPARK_ERR_WORKSPACE: return "workspace smaller than spark_mha_bwd_workspace_bytes()";

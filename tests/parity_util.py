@@ -2,6 +2,9 @@
 seeded inputs and measure the differences.  (Test code: may import both sides.)"""
 from __future__ import annotations
 
+import json
+import os
+
 import numpy as np
 
 import oracle
@@ -9,17 +12,27 @@ from paper_2502_12784_amd import synth
 
 # Tolerances (fp16 / bf16 inputs): max-abs on O and LSE, relative L2 on the gradients.
 #
-# O is compared as  |O - O_ref| <= TOL_ABS + half_ulp_out(O_ref) + operand_rounding, where
-#   * half_ulp_out is the unavoidable single rounding of the result to the 16-bit output
-#     type (up to |x| * 2^-8 for bf16, which alone exceeds 2e-3 once |x| >= 0.5);
-#   * operand_rounding: the method runs O = P V on 16-bit matrix cores (Sec. 3.2.2: P is
-#     converted to the operand type of the second contraction), so every P_ij is rounded to
-#     the type's precision first, a relative error of at most the unit roundoff u (2^-8 for
-#     bf16's 8 significant bits, 2^-11 for fp16's 11).  That perturbs O_i by at most
-#     u * sum_j P_ij |V_jk|; the oracle evaluates the sum exactly (a forward with |V|).
-# The raw max-abs error is always reported next to it.
+# O.  Three figures are computed for every case and printed:
+#   O_maxabs      raw max |O - O_ref|;
+#   O_excess_ulp  max (|O - O_ref| - half_ulp_out(O_ref)): what is left once the unavoidable single
+#                 rounding of the result to the 16-bit output type is set aside (up to |x| 2^-11 for
+#                 fp16, up to |x| 2^-8 for bf16, which alone exceeds 2e-3 once |x| >= 0.5);
+#   O_excess_op   the same with, in addition, the bound u * sum_j P_ij |V_jk| on what rounding P to the
+#                 16-bit operand type of the second contraction (Sec. 3.2.2) can do to O_i (u = 2^-8
+#                 for bf16's 8 significant bits; the oracle evaluates the sum exactly, a forward
+#                 with |V|).
+# Asserted:  fp16: O_excess_ulp <= 2e-3 (no operand term).  bf16: every element either meets that
+# too, or meets O_excess_op <= 2e-3; the number of elements that needed the operand term is
+# printed (O_needed_op) so that the looser reading is never used silently.
+#
+# Gradients: relative L2 per tensor, and a per-row check that one wrong row cannot hide in: for
+# every (batch, head, row)  ||g_row - ref_row|| <= TOL_ROW * (||ref_row|| + ROW_FLOOR * rms row
+# norm of the tensor).  A row that is zero, stale or belongs to another row has an error of the
+# order of its own norm and fails by a factor of 10 or more.
 TOL_ABS = 2e-3
 TOL_REL_L2 = 1e-2
+TOL_ROW = 5e-2
+ROW_FLOOR = 0.25
 
 
 def half_ulp(x64: np.ndarray, dtype: str) -> np.ndarray:
@@ -85,15 +98,16 @@ def run_oracle(inp, dtype, scale, causal, heads=None, dropout=None):
     s = float(np.float32(scale))
     ref = oracle.mha_bwd(arrs["Q"], arrs["K"], arrs["V"], arrs["dO"], s, causal, keep, ks)
     # bound on the effect of rounding P to the 16-bit operand type: u * P |V|
-    u = 2.0 ** -8 if dtype == synth.BF16 else 2.0 ** -11
-    ref["O_operand_rounding"] = u * oracle.mha_fwd(arrs["Q"], arrs["K"], np.abs(arrs["V"]), s, causal, False,
-                                                   keep, ks)[0]
+    # (bf16 only: fp16 cases are held to 2e-3 + half an output ulp without it)
+    if dtype == synth.BF16:
+        ref["O_operand_rounding"] = 2.0 ** -8 * oracle.mha_fwd(arrs["Q"], arrs["K"], np.abs(arrs["V"]), s,
+                                                               causal, False, keep, ks)[0]
     return ref
 
 
 def compare(gpu, ref, dtype, heads=None):
     """Return error measures; `heads` selects flat heads of the GPU tensors to match `ref`."""
-    out = {}
+    out = {"dtype": dtype}
 
     def pick(t):
         a = to_f64(t)
@@ -104,8 +118,11 @@ def compare(gpu, ref, dtype, heads=None):
     o_gpu, o_ref = pick(gpu["O"]), ref["O"]
     err = np.abs(o_gpu - o_ref)
     out["O_maxabs"] = float(err.max())
-    allow = half_ulp(o_ref, dtype) + ref.get("O_operand_rounding", 0.0)
-    out["O_excess"] = float((err - allow).max())  # must stay <= TOL_ABS
+    over_ulp = err - half_ulp(o_ref, dtype)
+    out["O_excess_ulp"] = float(over_ulp.max())
+    out["O_excess_op"] = float((over_ulp - ref.get("O_operand_rounding", 0.0)).max())
+    out["O_needed_op"] = int((over_ulp > TOL_ABS).sum())
+    out["O_elems"] = int(err.size)
     out["LSE_maxabs"] = float(np.abs(pick(gpu["LSE"]) - ref["LSE"]).max())
     for n in ("dQ", "dK", "dV"):
         g, r = pick(gpu[n]), ref[n]
@@ -114,14 +131,31 @@ def compare(gpu, ref, dtype, heads=None):
             # degenerate case with an exactly zero gradient (e.g. one key: dS = 0): compare the
             # RMS error with a unit-scale gradient instead of dividing by zero
             rn = np.sqrt(r.size)
+            row_rms = np.sqrt(r.shape[-1])
+        else:
+            row_rms = rn / np.sqrt(r.size / r.shape[-1])
         out[n + "_relL2"] = float(np.linalg.norm(g - r) / rn)
         out[n + "_finite"] = bool(np.isfinite(g).all())
+        row_err = np.linalg.norm(g - r, axis=-1)
+        row_ref = np.linalg.norm(r, axis=-1)
+        out[n + "_row"] = float((row_err / (row_ref + ROW_FLOOR * row_rms)).max())
+    log = os.environ.get("SPARK_PARITY_LOG")
+    if log:
+        with open(log, "a") as f:
+            f.write(json.dumps(out) + "\n")
     return out
 
 
 def assert_within_tolerance(m, label=""):
-    assert m["O_excess"] <= TOL_ABS, (label, m)
+    if m["dtype"] == synth.F16:
+        assert m["O_excess_ulp"] <= TOL_ABS, (label, m)
+    else:
+        assert m["O_excess_op"] <= TOL_ABS, (label, m)
+        if m["O_needed_op"]:
+            print("[parity] %s: %d of %d elements of O exceed 2e-3 + half an output ulp and are "
+                  "within the bf16 operand-rounding bound" % (label, m["O_needed_op"], m["O_elems"]))
     assert m["LSE_maxabs"] <= TOL_ABS, (label, m)
     for n in ("dQ", "dK", "dV"):
         assert m[n + "_finite"], (label, m)
         assert m[n + "_relL2"] <= TOL_REL_L2, (label, m)
+        assert m[n + "_row"] <= TOL_ROW, (label, m)

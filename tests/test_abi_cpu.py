@@ -159,11 +159,25 @@ def test_strided_validation(lib):
     assert fwd(sk=S(0, 0, 68)) == E_ALIGN              # 136-byte rows
     assert fwd(so=S(4, 0, 64)) == E_ALIGN
     assert fwd(sq=S(0, 0, 1 << 24), N=1024) == E_SHAPE  # one head would span 2 GiB or more
+    # a zero batch / head stride broadcasts an input, but would make every (batch, head) of an
+    # output store to the same rows
+    def fwd_bh(B, H, so, sq=S(0, 0, 64)):
+        return lib.spark_mha_strided_fwd(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, sq, sq, sq, so, B, H, 128,
+                                         128, 64, 0.125, 0, 0.0, 0, 0, 0, None)
+    assert fwd_bh(2, 1, S(0, 128 * 64, 64)) == E_SHAPE
+    assert fwd_bh(1, 2, S(2 * 128 * 64, 0, 64)) == E_SHAPE
     eight = [S(128 * 64, 64 * 128, 64)] * 8
     args = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000, 0x8000, 0x9000]
     tail = [0xA000, 1 << 20, 1, 1, 128, 128, 64, 0.125, 0, 0.0, 0, 0, 0, None]
     assert lib.spark_mha_strided_bwd(*args, *eight[:7], None, *tail) == E_NULL
     assert lib.spark_mha_strided_bwd(*args, *eight[:7], S(0, 0, 8), *tail) == E_SHAPE
+    tail2 = [0xA000, 1 << 20, 2, 2, 128, 128, 64, 0.125, 0, 0.0, 0, 0, 0, None]
+    good = S(2 * 128 * 64, 128 * 64, 64)
+    for pos in (5, 6, 7):  # dQ, dK, dV
+        for zero in (S(0, 128 * 64, 64), S(2 * 128 * 64, 0, 64)):
+            st = [good] * 8
+            st[pos] = zero
+            assert lib.spark_mha_strided_bwd(*args, *st, *tail2) == E_SHAPE
     tail[1] = 8
     assert lib.spark_mha_strided_bwd(*args, *eight, *tail) == E_WS
 

@@ -1,10 +1,11 @@
 """GPU parity: HIP path (through the C ABI) against the fp64 CPU oracle, same seeded inputs.
 
-Bar: |O - O_ref| <= 2e-3 + half an output ulp at |O_ref| (the output is rounded once to
-fp16/bf16) + u * P|V| (P is rounded to the 16-bit operand type before O = P V; u = 2^-8 bf16,
-2^-11 fp16; see parity_util), so 2e-3 bounds the rest of the computational error;
-|LSE - LSE_ref| <= 2e-3, and relative L2
-error <= 1e-2 for each of dQ, dK, dV.
+Bar (tests/parity_util.py): fp16: |O - O_ref| <= 2e-3 + half an output ulp at |O_ref| (the output
+is rounded once to 16 bits), and raw |O - O_ref| <= 2e-3 on the fp16 benchmark configurations;
+bf16: the same, except that elements which exceed it must lie within the bound u * P|V| on what
+rounding P to the bf16 operand type can do (their number is printed); |LSE - LSE_ref| <= 2e-3;
+relative L2 error <= 1e-2 for each of dQ, dK, dV, and every single row of them within 5e-2 of its
+own norm (plus a floor), so that one wrong row cannot hide in a whole-tensor norm.
 """
 import math
 
@@ -49,6 +50,7 @@ def test_config_C1_full():
     w = synth.WORKLOADS["C1"]
     m = _run_full(w.B, w.H, w.N, w.d, w.dtype, w.causal, w.seed, w.sigma_qk)
     pu.assert_within_tolerance(m, "C1")
+    assert m["O_maxabs"] <= pu.TOL_ABS, m  # fp16: the stated bound holds without any allowance
 
 
 def test_wide_logits_small():
@@ -70,6 +72,8 @@ def test_full_size_configs_sampled_heads(name):
     m = pu.compare(gpu, ref, w.dtype, heads=heads)
     print(f"\n[parity] {name} heads={heads}: {m}", flush=True)
     pu.assert_within_tolerance(m, name)
+    if w.dtype == synth.F16:
+        assert m["O_maxabs"] <= pu.TOL_ABS, m  # fp16: the stated bound holds without any allowance
     # properties that hold at any size, checked on every head of the GPU result
     dK = pu.to_f64(gpu["dK"]); dV = pu.to_f64(gpu["dV"])
     dO = synth.bits_to_f64(inp["dO"], w.dtype)
