@@ -227,6 +227,22 @@ int spark_mha_strided_bwd(const void* Q, const void* K, const void* V, const voi
                           float p_drop, unsigned long long seed, unsigned offset,
                           spark_dtype_t dtype, void* stream);
 
+/*
+ * Hardware self-check of the register layouts the kernels are written against (wave64
+ * 32x32x16 MFMA operands and accumulators, packed accumulator registers reused as the operand
+ * of a second MFMA -- the register form of the paper's Sec. 3.2.2 layout transform -- and the
+ * transposing LDS read).  One wave computes fixed small-integer products through those layouts.
+ *   out : out, device, 2304 floats:
+ *         [0, 1024)    C1 = A1 B1 (32x32, row-major), A1[i][k] = (37i + 11k + (ik mod 7)) mod 3 - 1
+ *                      for k < 16, B1[k][j] = (29k + 13j + (kj mod 5)) mod 5 - 2;
+ *         [1024, 2048) C2 = A2 C1, A2[m][r] = (17m + 7r + (mr mod 11)) mod 7 - 3, r < 32;
+ *         [2048, 2304) lane l = 16q + i of the wave, words t = 0..3: X[4q + t][16 + i] of the
+ *                      tile X[r][c] = 64r + c.
+ * All values are exact in both dtypes, so the expected output is exact.  Returns SPARK_OK,
+ * SPARK_ERR_NULL, SPARK_ERR_DTYPE or SPARK_ERR_LAUNCH.
+ */
+int spark_layout_probe(float* out, spark_dtype_t dtype, void* stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* spark_status_str(int status);
 

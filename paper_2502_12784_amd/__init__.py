@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     load_library,
     spark_dropout_mask,
     spark_dropout_threshold,
+    spark_layout_probe,
     spark_mha_bwd,
     spark_mha_bwd_workspace_bytes,
     spark_mha_cross_bwd,

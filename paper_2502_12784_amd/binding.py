@@ -20,7 +20,7 @@ EXPORTS = ("spark_mha_fwd", "spark_mha_bwd", "spark_mha_bwd_marked",
            "spark_mha_bwd_workspace_bytes", "spark_mha_cross_fwd", "spark_mha_cross_bwd",
            "spark_mha_cross_bwd_workspace_bytes", "spark_mha_dropout_fwd", "spark_mha_dropout_bwd",
            "spark_dropout_threshold", "spark_dropout_mask", "spark_mha_strided_fwd",
-           "spark_mha_strided_bwd", "spark_status_str")
+           "spark_mha_strided_bwd", "spark_status_str", "spark_layout_probe")
 
 _lib = None
 
@@ -88,6 +88,8 @@ def load_library() -> ctypes.CDLL:
                                                              f, u64, u32, i, vp])
     lib.spark_mha_bwd_marked.restype = i
     lib.spark_mha_bwd_marked.argtypes = lib.spark_mha_bwd.argtypes + [ctypes.POINTER(vp)]
+    lib.spark_layout_probe.restype = i
+    lib.spark_layout_probe.argtypes = [vp, i, vp]
     lib.spark_status_str.restype = ctypes.c_char_p
     lib.spark_status_str.argtypes = [i]
     _lib = lib
@@ -380,3 +382,11 @@ def spark_mha_bwd(Q, K, V, O, LSE, dO, scale: float, causal: bool, dQ=None, dK=N
     else:
         _check(lib.spark_mha_bwd_marked(*args, events[0].slice_ptr(events[1])))
     return dQ, dK, dV
+
+
+def spark_layout_probe(dtype_code: int):
+    """The 2304 floats of spark_layout_probe (see the header) as a device tensor."""
+    import torch
+    out = torch.full((2304,), float("nan"), dtype=torch.float32, device="cuda")
+    _check(load_library().spark_layout_probe(out.data_ptr(), int(dtype_code), _stream_ptr()))
+    return out

@@ -9,6 +9,7 @@
 
 #include "bwd_kernels.hpp"
 #include "fwd_kernel.hpp"
+#include "layout_probe.hpp"
 
 namespace {
 
@@ -387,6 +388,17 @@ int spark_dropout_mask(unsigned char* M, int B, int H, int Nq, int Nk, float p_d
   const unsigned grid = (unsigned)((total + 255) / 256);
   hipLaunchKernelGGL(dropout_mask_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
                      M, Nq, Nk, qblocks, kblocks, total, make_dropout(thr, seed, offset));
+  return hipGetLastError() == hipSuccess ? SPARK_OK : SPARK_ERR_LAUNCH;
+}
+
+int spark_layout_probe(float* out, spark_dtype_t dtype, void* stream) {
+  if (!out) return SPARK_ERR_NULL;
+  if (dtype != SPARK_F16 && dtype != SPARK_BF16) return SPARK_ERR_DTYPE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (dtype == SPARK_F16)
+    hipLaunchKernelGGL(layout_probe_kernel<_Float16>, dim3(1), dim3(64), 16 * 64 * 2, st, out);
+  else
+    hipLaunchKernelGGL(layout_probe_kernel<__bf16>, dim3(1), dim3(64), 16 * 64 * 2, st, out);
   return hipGetLastError() == hipSuccess ? SPARK_OK : SPARK_ERR_LAUNCH;
 }
 

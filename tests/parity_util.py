@@ -138,7 +138,12 @@ def compare(gpu, ref, dtype, heads=None):
         out[n + "_finite"] = bool(np.isfinite(g).all())
         row_err = np.linalg.norm(g - r, axis=-1)
         row_ref = np.linalg.norm(r, axis=-1)
-        out[n + "_row"] = float((row_err / (row_ref + ROW_FLOOR * row_rms)).max())
+        ratio = row_err / (row_ref + ROW_FLOOR * row_rms)
+        out[n + "_row"] = float(ratio.max())
+        worst = np.unravel_index(int(ratio.argmax()), ratio.shape)
+        out[n + "_row_at"] = [int(x) for x in worst]  # (batch or sampled head, head, row)
+        out[n + "_row_at_ref"] = float(row_ref[worst] / row_rms)  # that row's norm / rms row norm
+        out[n + "_row_at_err"] = float(row_err[worst] / row_rms)
     log = os.environ.get("SPARK_PARITY_LOG")
     if log:
         with open(log, "a") as f:
