@@ -123,6 +123,30 @@ int spark_mha_bwd_marked(const void* Q, const void* K, const void* V, const void
                          spark_dtype_t dtype, void* stream, void* const events[3]);
 
 /*
+ * spark_mha_bwd for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same kernels,
+ * same results bit for bit as spark_mha_bwd (self-attention, no dropout); the workspace (D and
+ * LSE * log2(e), 2 * B*H*N floats) is a fixed array inside the library's device image instead of
+ * an argument.  The call allocates and frees nothing and makes no allocating runtime call.
+ *   - Limit: B*H*N <= spark_mha_bwd_static_max_rows() (1 Mi rows: 8 MiB of scratch per GPU, held
+ *     by each GPU the library runs on until the process ends); larger problems return
+ *     SPARK_ERR_WORKSPACE and enqueue nothing.
+ *   - All calls on one GPU share that GPU's array: two calls whose kernels may overlap in time
+ *     (different streams, or several host threads) race on it and must be serialised by the
+ *     caller.  Calls on the same stream are ordered and safe.  Nothing in the array needs to
+ *     start at zero: every row a call reads was written by that call's first kernel.
+ *   - Arguments, layouts and error codes otherwise as for spark_mha_bwd; SPARK_ERR_LAUNCH also if
+ *     the runtime cannot resolve the array's device address.
+ */
+int spark_mha_bwd_static(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
+                         const void* dO, void* dQ, void* dK, void* dV,
+                         int B, int H, int N, int d, float scale, int causal,
+                         spark_dtype_t dtype, void* stream);
+
+/* Largest B*H*N spark_mha_bwd_static accepts. */
+size_t spark_mha_bwd_static_max_rows(void);
+
+/*
  * Cross-attention forward: Eq. 1 with S = scale * Q K^T of shape Nq x Nk (Sec. 2.1, second
  * attention layer of the decoder); same kernel, arithmetic and guarantees as spark_mha_fwd.
  *   Q       : in,  device, [B,H,Nq,d] dtype

@@ -20,7 +20,8 @@ EXPORTS = ("spark_mha_fwd", "spark_mha_bwd", "spark_mha_bwd_marked",
            "spark_mha_bwd_workspace_bytes", "spark_mha_cross_fwd", "spark_mha_cross_bwd",
            "spark_mha_cross_bwd_workspace_bytes", "spark_mha_dropout_fwd", "spark_mha_dropout_bwd",
            "spark_dropout_threshold", "spark_dropout_mask", "spark_mha_strided_fwd",
-           "spark_mha_strided_bwd", "spark_status_str", "spark_layout_probe")
+           "spark_mha_strided_bwd", "spark_status_str", "spark_mha_bwd_static",
+           "spark_mha_bwd_static_max_rows", "spark_layout_probe")
 
 _lib = None
 
@@ -88,6 +89,10 @@ def load_library() -> ctypes.CDLL:
                                                              f, u64, u32, i, vp])
     lib.spark_mha_bwd_marked.restype = i
     lib.spark_mha_bwd_marked.argtypes = lib.spark_mha_bwd.argtypes + [ctypes.POINTER(vp)]
+    lib.spark_mha_bwd_static.restype = i
+    lib.spark_mha_bwd_static.argtypes = [vp] * 9 + [i, i, i, i, f, i, i, vp]
+    lib.spark_mha_bwd_static_max_rows.restype = ctypes.c_size_t
+    lib.spark_mha_bwd_static_max_rows.argtypes = []
     lib.spark_layout_probe.restype = i
     lib.spark_layout_probe.argtypes = [vp, i, vp]
     lib.spark_status_str.restype = ctypes.c_char_p
@@ -381,6 +386,25 @@ def spark_mha_bwd(Q, K, V, O, LSE, dO, scale: float, causal: bool, dQ=None, dK=N
         _check(lib.spark_mha_bwd(*args))
     else:
         _check(lib.spark_mha_bwd_marked(*args, events[0].slice_ptr(events[1])))
+    return dQ, dK, dV
+
+
+def spark_mha_bwd_static_max_rows() -> int:
+    return int(load_library().spark_mha_bwd_static_max_rows())
+
+
+def spark_mha_bwd_static(Q, K, V, O, LSE, dO, scale: float, causal: bool, dQ, dK, dV):
+    """spark_mha_bwd without a workspace argument: the library's own fixed scratch array is used.
+    The outputs must be passed in (the point of this entry point is that nothing is allocated)."""
+    import torch
+    lib = load_library()
+    B, H, N, d = Q.shape
+    for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O"), (dO, "dO"), (dQ, "dQ"), (dK, "dK"), (dV, "dV")):
+        _require(t, (B, H, N, d), Q.dtype, n)
+    _require(LSE, (B, H, N), torch.float32, "LSE")
+    _check(lib.spark_mha_bwd_static(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(),
+                                    dO.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), B, H, N, d,
+                                    float(scale), int(bool(causal)), _dtype_code(Q), _stream_ptr()))
     return dQ, dK, dV
 
 

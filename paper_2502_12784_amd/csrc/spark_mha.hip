@@ -11,9 +11,28 @@
 #include "fwd_kernel.hpp"
 #include "layout_probe.hpp"
 
+// Scratch memory of spark_mha_bwd_static: the backward's workspace (D and LSE * log2(e)) for callers
+// that cannot allocate.  One copy per GPU, at its own address on each, held until the process ends.
+// In host code this name is only a handle for hipGetSymbolAddress, never a device address.
+#define SPARK_STATIC_SCRATCH_BYTES (8u << 20)
+static __device__ __align__(256) unsigned char scratch[SPARK_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using namespace spark;
+
+// Device address of `scratch` on the current device, looked up once per device with that device
+// current and kept; nullptr if the runtime cannot resolve it.
+void* static_scratch_ptr() {
+  static std::atomic<void*> ptrs[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  void* p = ptrs[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+  ptrs[dev].store(p, std::memory_order_release);  // every thread resolves the same address
+  return p;
+}
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -374,6 +393,21 @@ int spark_mha_bwd_marked(const void* Q, const void* K, const void* V, const void
   return run_bwd(p, Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, events);
 }
 
+size_t spark_mha_bwd_static_max_rows(void) { return SPARK_STATIC_SCRATCH_BYTES / (2 * sizeof(float)); }
+
+int spark_mha_bwd_static(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
+                         const void* dO, void* dQ, void* dK, void* dV, int B, int H, int N, int d,
+                         float scale, int causal, spark_dtype_t dtype, void* stream) {
+  if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV) return SPARK_ERR_NULL;
+  Problem p;
+  const int rc = make_problem(&p, B, H, N, N, d, scale, causal, 0, 0, 0, dtype, stream);
+  if (rc != SPARK_OK) return rc;
+  if (workspace_bytes(B, H, N) > SPARK_STATIC_SCRATCH_BYTES) return SPARK_ERR_WORKSPACE;
+  void* ws = static_scratch_ptr();
+  if (!ws) return SPARK_ERR_LAUNCH;
+  return run_bwd(p, Q, K, V, O, LSE, dO, dQ, dK, dV, ws, SPARK_STATIC_SCRATCH_BYTES, nullptr);
+}
+
 int spark_dropout_threshold(float p_drop) { return drop_threshold(p_drop); }
 
 int spark_dropout_mask(unsigned char* M, int B, int H, int Nq, int Nk, float p_drop,
@@ -412,7 +446,9 @@ const char* spark_status_str(int status) {
              "nonzero batch/head strides for outputs, sizes within the documented limits)";
     case SPARK_ERR_DTYPE: return "unsupported dtype (need SPARK_F16 or SPARK_BF16)";
     case SPARK_ERR_ALIGN: return "a pointer or stride is not 16-byte aligned";
-    case SPARK_ERR_WORKSPACE: return "workspace smaller than spark_mha_bwd_workspace_bytes()";
+    case SPARK_ERR_WORKSPACE:
+      return "workspace smaller than spark_mha_bwd_workspace_bytes(), or B*H*N above "
+             "spark_mha_bwd_static_max_rows() for spark_mha_bwd_static";
     case SPARK_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
     default: return "unknown status";
   }

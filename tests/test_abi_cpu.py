@@ -90,6 +90,19 @@ def test_bwd_validation(lib):
     assert _bwd(lib, fn="spark_mha_bwd_marked", extra=(evs,)) == E_NULL
 
 
+def test_static_workspace_entry_point_validation(lib):
+    """spark_mha_bwd_static: refusals that happen before the device is touched."""
+    def call(q=0x1000, B=1, H=1, N=128, d=64, dtype=0):
+        return lib.spark_mha_bwd_static(q, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000, 0x8000, 0x9000,
+                                        B, H, N, d, 0.125, 0, dtype, None)
+    rows = pkg.spark_mha_bwd_static_max_rows()
+    assert rows == 1 << 20
+    assert call(q=None) == E_NULL
+    assert call(d=100) == E_SHAPE
+    assert call(dtype=3) == E_DTYPE
+    assert call(B=2, H=8, N=(rows // 16) + 1) == E_WS   # one row too many for the fixed scratch array
+
+
 def test_cross_validation(lib):
     def fwd(Nq=128, Nk=96, causal=0, **kw):
         a = dict(q=0x1000, k=0x2000, v=0x3000, o=0x4000, lse=0x5000, B=1, H=1, d=64, scale=0.125, dtype=0)
