@@ -42,8 +42,7 @@ def read_traffic(workload: str, kernel: str):
 
 def time_workload(w, steps, warmup, dropout=None):
     """Average ms per step (wall clock) and per kernel (HIP events on the launch stream).
-    dropout: None, or (p_drop, seed, offset): the dropout entry points; then the backward is
-    timed as a whole (key "bwd") instead of per kernel."""
+    dropout: None, or (p_drop, seed, offset): the dropout entry points."""
     import torch
     from paper_2502_12784_amd import (HipEvents, spark_mha_bwd, spark_mha_dropout_bwd,
                                       spark_mha_dropout_fwd, spark_mha_fwd, synth)
@@ -71,12 +70,8 @@ def time_workload(w, steps, warmup, dropout=None):
                           events=None if ev is None else (ev, base + 1))
         else:
             spark_mha_dropout_fwd(Q, K, V, w.scale, w.causal, *dropout, O=O, LSE=LSE)
-            if ev is not None:
-                ev.record(base + 1)
             spark_mha_dropout_bwd(Q, K, V, O, LSE, dO, w.scale, w.causal, *dropout, dQ=dQ, dK=dK,
-                                  dV=dV, workspace=ws)
-            if ev is not None:
-                ev.record(base + 3)
+                                  dV=dV, workspace=ws, events=None if ev is None else (ev, base + 1))
 
     for _ in range(warmup):
         step()
@@ -89,13 +84,10 @@ def time_workload(w, steps, warmup, dropout=None):
         step(ev, 4 * s)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    k = {"fwd": 0.0, "bwd": 0.0} if dropout else {"fwd": 0.0, "bwd_dq": 0.0, "bwd_dkdv": 0.0}
+    k = {"fwd": 0.0, "bwd_dq": 0.0, "bwd_dkdv": 0.0}
     for s in range(steps):
         b = 4 * s
         k["fwd"] += ev.elapsed_ms(b, b + 1)
-        if dropout:
-            k["bwd"] += ev.elapsed_ms(b + 1, b + 3)
-            continue
         k["bwd_dq"] += ev.elapsed_ms(b + 1, b + 2)
         k["bwd_dkdv"] += ev.elapsed_ms(b + 2, b + 3)
     # fwd+bwd of each step from the first to the last event of the step (GPU time on the stream)
@@ -105,6 +97,57 @@ def time_workload(w, steps, warmup, dropout=None):
     k["step_median"] = per_step[len(per_step) // 2]
     k["step_min"] = per_step[0]
     return wall / steps * 1e3, k
+
+
+def time_bwd_variants(w, steps, warmup):
+    """The two backward variants on the same resident inputs, timed with HIP events on the launch
+    stream around the whole backward: the default (separate deterministic dQ pass + dK/dV kernel)
+    and the paper's own (Sec. 3.3: one fused kernel, dQ by fp32 atomic adds, plus the D / clear
+    and the convert kernels).  Alternating, so that both see the same clock and cache state."""
+    import torch
+    from paper_2502_12784_amd import (HipEvents, spark_mha_bwd, spark_mha_bwd_atomic,
+                                      spark_mha_bwd_atomic_workspace_bytes, spark_mha_fwd, synth)
+    from paper_2502_12784_amd.binding import _dtype_code, spark_mha_bwd_workspace_bytes
+
+    def dev(bits):
+        t = torch.from_numpy(bits.view(np.int16)).cuda()
+        return t.view(torch.float16 if w.dtype == synth.F16 else torch.bfloat16)
+
+    inp = synth.make_workload_inputs(w)
+    Q, K, V, dO = (dev(inp[n]) for n in ("Q", "K", "V", "dO"))
+    del inp
+    O, LSE = spark_mha_fwd(Q, K, V, w.scale, w.causal)
+    dQ, dK, dV = (torch.empty_like(Q) for _ in range(3))
+    code = _dtype_code(Q)
+    ws = torch.empty(max(16, spark_mha_bwd_workspace_bytes(w.B, w.H, w.N, w.d, code)), dtype=torch.uint8, device="cuda")
+    wsa = torch.empty(spark_mha_bwd_atomic_workspace_bytes(w.B, w.H, w.N, w.N, w.d, code), dtype=torch.uint8,
+                      device="cuda")
+
+    def two_kernel():
+        spark_mha_bwd(Q, K, V, O, LSE, dO, w.scale, w.causal, dQ=dQ, dK=dK, dV=dV, workspace=ws)
+
+    def atomic():
+        spark_mha_bwd_atomic(Q, K, V, O, LSE, dO, w.scale, w.causal, dQ=dQ, dK=dK, dV=dV, workspace=wsa)
+
+    for _ in range(warmup):
+        two_kernel()
+        atomic()
+    torch.cuda.synchronize()
+    ev = HipEvents(3 * steps)
+    for s in range(steps):
+        ev.record(3 * s)
+        two_kernel()
+        ev.record(3 * s + 1)
+        atomic()
+        ev.record(3 * s + 2)
+    torch.cuda.synchronize()
+    t2 = sum(ev.elapsed_ms(3 * s, 3 * s + 1) for s in range(steps)) / steps
+    ta = sum(ev.elapsed_ms(3 * s + 1, 3 * s + 2) for s in range(steps)) / steps
+    ev.close()
+    return {"two_kernel_ms": t2, "atomic_ms": ta,
+            "two_kernel_bwd_tflops": w.bwd_flops / (t2 * 1e-3) / 1e12,
+            "atomic_bwd_tflops": w.bwd_flops / (ta * 1e-3) / 1e12,
+            "atomic_adds_GB": w.B * w.H * ((w.N + 127) // 128) * w.N * w.d * 4 * (0.5 if w.causal else 1.0) / 1e9}
 
 
 def cpu_baseline(w, budget_s=12.0):
@@ -149,6 +192,9 @@ def main():
                     help="also time the paper's own grid (Sec. 4.1: hidden 2048, d in {64,128}, "
                          "N in {512..16384}, B = 16384/N, both mask settings, fp16, no dropout) "
                          "and add it as an extra field")
+    ap.add_argument("--bwd-variants", action="store_true",
+                    help="also time the paper's atomic-dQ backward against the default two-kernel backward "
+                         "on the workload (extra field)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run 5 plain device copies of 256 MiB (reads 256 MiB, writes 256 MiB each) "
                          "so FETCH_SIZE / WRITE_SIZE counters can be scaled against a known size")
@@ -207,7 +253,10 @@ def main():
                                dropout=(0.1, 0x9E3779B97F4A7C15, 1))
         out["with_dropout_0.1"] = {"value": flops_step / (md * 1e-3) / 1e12, "unit": "TFLOP/s", "ms_per_step": md,
                                    "fwd_tflops": w.fwd_flops / (kd["fwd"] * 1e-3) / 1e12,
-                                   "bwd_tflops": w.bwd_flops / (kd["bwd"] * 1e-3) / 1e12}
+                                   "bwd_tflops": w.bwd_flops / ((kd["bwd_dq"] + kd["bwd_dkdv"]) * 1e-3) / 1e12,
+                                   "kernel_ms": {n: v for n, v in kd.items() if not n.startswith("step_")}}
+    if args.bwd_variants:
+        out["bwd_variants"] = time_bwd_variants(w, max(5, args.steps // 2), max(2, args.warmup // 2))
     if args.all:
         others = {}
         for name, ww in synth.WORKLOADS.items():
@@ -235,7 +284,7 @@ def main():
                                   "tflops": (ww.fwd_flops + ww.bwd_flops) / (m2 * 1e-3) / 1e12,
                                   "dropout_0.1": {
                                       "fwd_tflops": ww.fwd_flops / (k3["fwd"] * 1e-3) / 1e12,
-                                      "bwd_tflops": ww.bwd_flops / (k3["bwd"] * 1e-3) / 1e12,
+                                      "bwd_tflops": ww.bwd_flops / ((k3["bwd_dq"] + k3["bwd_dkdv"]) * 1e-3) / 1e12,
                                       "tflops": (ww.fwd_flops + ww.bwd_flops) / (m3 * 1e-3) / 1e12}})
         out["paper_sweep"] = sweep
     if not args.no_cpu:

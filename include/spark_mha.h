@@ -123,6 +123,28 @@ int spark_mha_bwd_marked(const void* Q, const void* K, const void* V, const void
                          spark_dtype_t dtype, void* stream, void* const events[3]);
 
 /*
+ * The backward exactly as the paper builds it (Sec. 3.3): ONE fused kernel whose workgroups each own a
+ * slice of dK and dV, accumulate them on chip, and add their contributions to dQ into HBM with fp32
+ * atomic adds in every iteration (five contractions executed for five counted), preceded by a
+ * kernel that forms D = rowsum(dO o O) and clears the fp32 dQ accumulator and followed by one that
+ * scales and rounds the accumulator to dQ.  Same arguments, layouts and error codes as
+ * spark_mha_cross_bwd (no dropout); the workspace additionally holds the accumulator:
+ * spark_mha_bwd_atomic_workspace_bytes(...) = two fp32 [B,H,Nq] arrays, padded to 256 bytes, plus
+ * fp32 [B,H,Nq,d].  dK and dV are reproducible bit for bit; dQ differs from run to run in its
+ * last bits, because the order of the atomic adds is not fixed (several results are correct).
+ * Provided for comparison: on MI355X it is the slower variant (the chip retires fp32 atomic adds at
+ * about 1.3 TB/s, and every element of dQ receives Nk/128 of them), so spark_mha_bwd and the
+ * other entry points use the separate deterministic dQ pass.
+ */
+size_t spark_mha_bwd_atomic_workspace_bytes(int B, int H, int Nq, int Nk, int d, spark_dtype_t dtype);
+
+int spark_mha_bwd_atomic(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
+                         const void* dO, void* dQ, void* dK, void* dV,
+                         void* workspace, size_t workspace_bytes,
+                         int B, int H, int Nq, int Nk, int d, float scale, int causal,
+                         spark_dtype_t dtype, void* stream);
+
+/*
  * spark_mha_bwd for callers that cannot allocate device memory or pass a workspace: code under HIP
  * graph capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same kernels,
  * same results bit for bit as spark_mha_bwd (self-attention, no dropout); the workspace (D and
@@ -204,6 +226,18 @@ int spark_mha_dropout_bwd(const void* Q, const void* K, const void* V, const voi
                           int B, int H, int Nq, int Nk, int d, float scale, int causal,
                           float p_drop, unsigned long long seed, unsigned offset,
                           spark_dtype_t dtype, void* stream);
+
+/*
+ * spark_mha_dropout_bwd with profiling marks (see spark_mha_bwd_marked): identical work, plus the
+ * caller's three HIP events recorded on `stream` before the dQ kernel, after it, and after the
+ * dK/dV kernel.
+ */
+int spark_mha_dropout_bwd_marked(const void* Q, const void* K, const void* V, const void* O,
+                                 const float* LSE, const void* dO, void* dQ, void* dK, void* dV,
+                                 void* workspace, size_t workspace_bytes,
+                                 int B, int H, int Nq, int Nk, int d, float scale, int causal,
+                                 float p_drop, unsigned long long seed, unsigned offset,
+                                 spark_dtype_t dtype, void* stream, void* const events[3]);
 
 /* The 8-bit threshold a dropout rate is realised with (see above), or -1 if p_drop is invalid. */
 int spark_dropout_threshold(float p_drop);

@@ -13,6 +13,8 @@ from .binding import (  # noqa: F401
     spark_dropout_threshold,
     spark_layout_probe,
     spark_mha_bwd,
+    spark_mha_bwd_atomic,
+    spark_mha_bwd_atomic_workspace_bytes,
     spark_mha_bwd_static,
     spark_mha_bwd_static_max_rows,
     spark_mha_bwd_workspace_bytes,

@@ -21,7 +21,8 @@ EXPORTS = ("spark_mha_fwd", "spark_mha_bwd", "spark_mha_bwd_marked",
            "spark_mha_cross_bwd_workspace_bytes", "spark_mha_dropout_fwd", "spark_mha_dropout_bwd",
            "spark_dropout_threshold", "spark_dropout_mask", "spark_mha_strided_fwd",
            "spark_mha_strided_bwd", "spark_status_str", "spark_mha_bwd_static",
-           "spark_mha_bwd_static_max_rows", "spark_layout_probe")
+           "spark_mha_bwd_static_max_rows", "spark_layout_probe", "spark_mha_bwd_atomic",
+           "spark_mha_bwd_atomic_workspace_bytes", "spark_mha_dropout_bwd_marked")
 
 _lib = None
 
@@ -77,6 +78,8 @@ def load_library() -> ctypes.CDLL:
     lib.spark_mha_dropout_bwd.restype = i
     lib.spark_mha_dropout_bwd.argtypes = ([vp] * 10 + [ctypes.c_size_t, i, i, i, i, i, f, i, f, u64,
                                                       u32, i, vp])
+    lib.spark_mha_dropout_bwd_marked.restype = i
+    lib.spark_mha_dropout_bwd_marked.argtypes = lib.spark_mha_dropout_bwd.argtypes + [ctypes.POINTER(vp)]
     lib.spark_dropout_threshold.restype = i
     lib.spark_dropout_threshold.argtypes = [f]
     lib.spark_dropout_mask.restype = i
@@ -93,6 +96,10 @@ def load_library() -> ctypes.CDLL:
     lib.spark_mha_bwd_static.argtypes = [vp] * 9 + [i, i, i, i, f, i, i, vp]
     lib.spark_mha_bwd_static_max_rows.restype = ctypes.c_size_t
     lib.spark_mha_bwd_static_max_rows.argtypes = []
+    lib.spark_mha_bwd_atomic_workspace_bytes.restype = ctypes.c_size_t
+    lib.spark_mha_bwd_atomic_workspace_bytes.argtypes = [i, i, i, i, i, i]
+    lib.spark_mha_bwd_atomic.restype = i
+    lib.spark_mha_bwd_atomic.argtypes = lib.spark_mha_cross_bwd.argtypes
     lib.spark_layout_probe.restype = i
     lib.spark_layout_probe.argtypes = [vp, i, vp]
     lib.spark_status_str.restype = ctypes.c_char_p
@@ -208,14 +215,15 @@ def spark_mha_dropout_fwd(Q, K, V, scale: float, causal: bool, p_drop: float, se
 
 
 def spark_mha_dropout_bwd(Q, K, V, O, LSE, dO, scale: float, causal: bool, p_drop: float,
-                          seed: int, offset: int, dQ=None, dK=None, dV=None, workspace=None):
-    """Backward of spark_mha_dropout_fwd; pass the same (p_drop, seed, offset)."""
+                          seed: int, offset: int, dQ=None, dK=None, dV=None, workspace=None, events=None):
+    """Backward of spark_mha_dropout_fwd; pass the same (p_drop, seed, offset).
+    ``events``: optional ``(HipEvents, first_index)`` -> spark_mha_dropout_bwd_marked."""
     return spark_mha_cross_bwd(Q, K, V, O, LSE, dO, scale, causal, dQ, dK, dV, workspace,
-                               dropout=(p_drop, seed, offset))
+                               dropout=(p_drop, seed, offset), events=events)
 
 
 def spark_mha_cross_bwd(Q, K, V, O, LSE, dO, scale: float, causal: bool = False, dQ=None,
-                        dK=None, dV=None, workspace=None, dropout=None):
+                        dK=None, dV=None, workspace=None, dropout=None, events=None):
     """dQ [B,H,Nq,d], dK, dV [B,H,Nk,d] for the problem of spark_mha_cross_fwd.
     dropout: None, or (p_drop, seed, offset) -> spark_mha_dropout_bwd."""
     import torch
@@ -245,8 +253,12 @@ def spark_mha_cross_bwd(Q, K, V, O, LSE, dO, scale: float, causal: bool = False,
                                        _stream_ptr()))
     else:
         p_drop, seed, offset = dropout
-        _check(lib.spark_mha_dropout_bwd(*ptrs, B, H, Nq, Nk, d, float(scale), int(bool(causal)),
-                                         float(p_drop), int(seed), int(offset), code, _stream_ptr()))
+        tail = (B, H, Nq, Nk, d, float(scale), int(bool(causal)), float(p_drop), int(seed), int(offset),
+                code, _stream_ptr())
+        if events is None:
+            _check(lib.spark_mha_dropout_bwd(*ptrs, *tail))
+        else:
+            _check(lib.spark_mha_dropout_bwd_marked(*ptrs, *tail, events[0].slice_ptr(events[1])))
     return dQ, dK, dV
 
 
@@ -414,3 +426,37 @@ def spark_layout_probe(dtype_code: int):
     out = torch.full((2304,), float("nan"), dtype=torch.float32, device="cuda")
     _check(load_library().spark_layout_probe(out.data_ptr(), int(dtype_code), _stream_ptr()))
     return out
+
+
+def spark_mha_bwd_atomic_workspace_bytes(B: int, H: int, Nq: int, Nk: int, d: int, dtype_code: int) -> int:
+    return int(load_library().spark_mha_bwd_atomic_workspace_bytes(B, H, Nq, Nk, d, dtype_code))
+
+
+def spark_mha_bwd_atomic(Q, K, V, O, LSE, dO, scale: float, causal: bool = False, dQ=None, dK=None,
+                         dV=None, workspace=None):
+    """The paper's own backward: one fused kernel, dQ accumulated in HBM with fp32 atomic adds."""
+    import torch
+    lib = load_library()
+    B, H, Nq, d = Q.shape
+    Nk = K.shape[2]
+    for t, n in ((Q, "Q"), (O, "O"), (dO, "dO")):
+        _require(t, (B, H, Nq, d), Q.dtype, n)
+    for t, n in ((K, "K"), (V, "V")):
+        _require(t, (B, H, Nk, d), Q.dtype, n)
+    _require(LSE, (B, H, Nq), torch.float32, "LSE")
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(K) if dV is None else dV
+    _require(dQ, (B, H, Nq, d), Q.dtype, "dQ")
+    for t, n in ((dK, "dK"), (dV, "dV")):
+        _require(t, (B, H, Nk, d), Q.dtype, n)
+    code = _dtype_code(Q)
+    need = spark_mha_bwd_atomic_workspace_bytes(B, H, Nq, Nk, d, code)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
+    wbytes = workspace.numel() * workspace.element_size()
+    _check(lib.spark_mha_bwd_atomic(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(),
+                                    dO.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
+                                    workspace.data_ptr(), wbytes, B, H, Nq, Nk, d, float(scale),
+                                    int(bool(causal)), code, _stream_ptr()))
+    return dQ, dK, dV

@@ -7,6 +7,7 @@
 #include <stdint.h>
 #include <atomic>
 
+#include "bwd_atomic_kernels.hpp"
 #include "bwd_kernels.hpp"
 #include "fwd_kernel.hpp"
 #include "layout_probe.hpp"
@@ -214,6 +215,44 @@ int launch_bwd(const Problem& p, const void* Q, const void* K, const void* V, co
   return SPARK_OK;
 }
 
+size_t workspace_bytes(int B, int H, int Nq) { return 2 * (size_t)B * H * Nq * sizeof(float); }
+size_t workspace_bytes_stats(int B, int H, int Nq) { return workspace_bytes(B, H, Nq); }
+
+// The paper's own backward (Sec. 3.3): prepare (D, LSE * log2(e), cleared fp32 dQ accumulator), one
+// fused kernel that adds dQ contributions with atomics, conversion of the accumulator to dQ.
+size_t atomic_dq_offset(int B, int H, int Nq) { return (workspace_bytes_stats(B, H, Nq) + 255) & ~(size_t)255; }
+
+template <typename T, int D, bool CAUSAL>
+int launch_bwd_atomic(const Problem& p, const void* Q, const void* K, const void* V, const void* O,
+                      const float* LSE, const void* dO, void* dQ, void* dK, void* dV, void* workspace) {
+  const int BH = p.B * p.H;
+  const long long rows = (long long)BH * p.Nq;
+  float* Dws = static_cast<float*>(workspace);
+  float* LSE2ws = Dws + rows;
+  float* dQacc = reinterpret_cast<float*>(static_cast<char*>(workspace) + atomic_dq_offset(p.B, p.H, p.Nq));
+  hipLaunchKernelGGL(mha_bwd_prep_kernel<T>, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, p.st,
+                     static_cast<const T*>(O), static_cast<const T*>(dO), LSE, Dws, LSE2ws, dQacc, p.mo, p.mdo,
+                     p.H, p.Nq, p.d, rows);
+  if (hipGetLastError() != hipSuccess) return SPARK_ERR_LAUNCH;
+  {
+    using C = BwdAtomicCfg<D>;
+    auto kernel = mha_bwd_fused_atomic_kernel<T, D, CAUSAL>;
+    static std::atomic<uint64_t> ready{0};
+    const int attr = ensure_smem(kernel, C::SMEM, ready);
+    if (attr != SPARK_OK) return attr;
+    const int nkt = (p.Nk + C::BN - 1) / C::BN;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nkt))), dim3(256), C::SMEM, p.st,
+                       static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
+                       static_cast<const T*>(dO), LSE2ws, Dws, dQacc, static_cast<T*>(dK), static_cast<T*>(dV),
+                       p.mq, p.mk, p.mv, p.mdo, p.mdk, p.mdv, p.H, p.Nq, p.Nk, p.d, nkt, p.scale);
+    if (hipGetLastError() != hipSuccess) return SPARK_ERR_LAUNCH;
+  }
+  const long long chunks = rows * (p.d >> 3);
+  hipLaunchKernelGGL(mha_bwd_dq_convert_kernel<T>, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, p.st,
+                     dQacc, static_cast<T*>(dQ), p.mdq, p.H, p.Nq, p.d, p.scale, chunks);
+  return hipGetLastError() == hipSuccess ? SPARK_OK : SPARK_ERR_LAUNCH;
+}
+
 // Expand the (dtype, d, causal, dropout) runtime tuple into a template instantiation.
 #define SPARK_DISPATCH_CD(FN, T, D, ...)                                                    \
   do {                                                                                      \
@@ -256,8 +295,6 @@ int run_fwd(const Problem& p, const void* Q, const void* K, const void* V, void*
     return SPARK_ERR_ALIGN;
   SPARK_DISPATCH(launch_fwd, p, Q, K, V, O, LSE);
 }
-
-size_t workspace_bytes(int B, int H, int Nq) { return 2 * (size_t)B * H * Nq * sizeof(float); }
 
 int run_bwd(const Problem& p, const void* Q, const void* K, const void* V, const void* O,
             const float* LSE, const void* dO, void* dQ, void* dK, void* dV, void* workspace,
@@ -406,6 +443,54 @@ int spark_mha_bwd_static(const void* Q, const void* K, const void* V, const void
   void* ws = static_scratch_ptr();
   if (!ws) return SPARK_ERR_LAUNCH;
   return run_bwd(p, Q, K, V, O, LSE, dO, dQ, dK, dV, ws, SPARK_STATIC_SCRATCH_BYTES, nullptr);
+}
+
+size_t spark_mha_bwd_atomic_workspace_bytes(int B, int H, int Nq, int Nk, int d, spark_dtype_t dtype) {
+  if (check_common(B, H, Nq, Nk, d, 1.0f, 0, (int)dtype) != SPARK_OK) return 0;
+  return atomic_dq_offset(B, H, Nq) + (size_t)B * H * Nq * d * sizeof(float);
+}
+
+int spark_mha_bwd_atomic(const void* Q, const void* K, const void* V, const void* O, const float* LSE,
+                         const void* dO, void* dQ, void* dK, void* dV, void* workspace,
+                         size_t workspace_bytes, int B, int H, int Nq, int Nk, int d, float scale,
+                         int causal, spark_dtype_t dtype, void* stream) {
+  if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV || !workspace) return SPARK_ERR_NULL;
+  Problem p;
+  const int rc = make_problem(&p, B, H, Nq, Nk, d, scale, causal, 0, 0, 0, dtype, stream);
+  if (rc != SPARK_OK) return rc;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(LSE) ||
+      !aligned16(dO) || !aligned16(dQ) || !aligned16(dK) || !aligned16(dV) || !aligned16(workspace))
+    return SPARK_ERR_ALIGN;
+  // the two elementwise kernels are gridded over rows / 16 and over 8-element chunks / 256
+  if (((int64_t)B * H * Nq + 15) / 16 >= (int64_t)1 << 31 ||
+      ((int64_t)B * H * Nq * (d >> 3) + 255) / 256 >= (int64_t)1 << 31)
+    return SPARK_ERR_SHAPE;
+  if (workspace_bytes < spark_mha_bwd_atomic_workspace_bytes(B, H, Nq, Nk, d, dtype)) return SPARK_ERR_WORKSPACE;
+#define SPARK_ATOMIC_CD(T, D)                                                                          \
+  return p.causal ? launch_bwd_atomic<T, D, true>(p, Q, K, V, O, LSE, dO, dQ, dK, dV, workspace)       \
+                  : launch_bwd_atomic<T, D, false>(p, Q, K, V, O, LSE, dO, dQ, dK, dV, workspace)
+  if (p.dtype == SPARK_F16) {
+    if (p.d <= 64) SPARK_ATOMIC_CD(_Float16, 64);
+    SPARK_ATOMIC_CD(_Float16, 128);
+  }
+  if (p.d <= 64) SPARK_ATOMIC_CD(__bf16, 64);
+  SPARK_ATOMIC_CD(__bf16, 128);
+#undef SPARK_ATOMIC_CD
+}
+
+int spark_mha_dropout_bwd_marked(const void* Q, const void* K, const void* V, const void* O,
+                                 const float* LSE, const void* dO, void* dQ, void* dK, void* dV,
+                                 void* workspace, size_t workspace_bytes, int B, int H, int Nq, int Nk,
+                                 int d, float scale, int causal, float p_drop, unsigned long long seed,
+                                 unsigned offset, spark_dtype_t dtype, void* stream,
+                                 void* const events[3]) {
+  if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV || !workspace) return SPARK_ERR_NULL;
+  if (!events || !events[0] || !events[1] || !events[2]) return SPARK_ERR_NULL;
+  Problem p;
+  const int rc = make_problem(&p, B, H, Nq, Nk, d, scale, causal, drop_threshold(p_drop), seed,
+                              offset, dtype, stream);
+  if (rc != SPARK_OK) return rc;
+  return run_bwd(p, Q, K, V, O, LSE, dO, dQ, dK, dV, workspace, workspace_bytes, events);
 }
 
 int spark_dropout_threshold(float p_drop) { return drop_threshold(p_drop); }

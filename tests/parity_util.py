@@ -27,12 +27,17 @@ from paper_2502_12784_amd import synth
 #
 # Gradients: relative L2 per tensor, and a per-row check that one wrong row cannot hide in: for
 # every (batch, head, row)  ||g_row - ref_row|| <= TOL_ROW * (||ref_row|| + ROW_FLOOR * rms row
-# norm of the tensor).  A row that is zero, stale or belongs to another row has an error of the
-# order of its own norm and fails by a factor of 10 or more.
+# norm of the tensor), TOL_ROW = 2e-2 for fp16 and 5e-2 for bf16.  A row that is zero, stale or
+# belongs to another row has an error of the order of its own norm: it fails unless its norm is
+# below a tenth (fp16: a twentieth) of the typical row's.  The absolute part (ROW_FLOOR) is
+# needed because the backward consumes the forward's 16-bit O: D = rowsum(dO o O) carries O's
+# rounding, and in dS = P o (dP - D) that error does not shrink with the row.  The extreme case is
+# causal row 0, whose exact dQ is zero (one key: dP = D); measured there: up to 0.047 x the rms
+# row norm in bf16 (N = 4096, d = 128, with dropout), 0.002 in fp16.
 TOL_ABS = 2e-3
 TOL_REL_L2 = 1e-2
-TOL_ROW = 5e-2
-ROW_FLOOR = 0.25
+TOL_ROW = {synth.F16: 2e-2, synth.BF16: 5e-2}
+ROW_FLOOR = 2.0
 
 
 def half_ulp(x64: np.ndarray, dtype: str) -> np.ndarray:
@@ -163,4 +168,4 @@ def assert_within_tolerance(m, label=""):
     for n in ("dQ", "dK", "dV"):
         assert m[n + "_finite"], (label, m)
         assert m[n + "_relL2"] <= TOL_REL_L2, (label, m)
-        assert m[n + "_row"] <= TOL_ROW, (label, m)
+        assert m[n + "_row"] <= TOL_ROW[m["dtype"]], (label, m)
