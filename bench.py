@@ -150,6 +150,42 @@ def time_bwd_variants(w, steps, warmup):
             "atomic_adds_GB": w.B * w.H * ((w.N + 127) // 128) * w.N * w.d * 4 * (0.5 if w.causal else 1.0) / 1e9}
 
 
+def hbm_floor_us(w, which):
+    """Time to move the algorithmic bytes of one pass at 8 TB/s: forward reads Q, K, V and writes O,
+    LSE; backward reads Q, K, V, O, dO, LSE and writes dQ, dK, dV (plus D and LSE*log2(e) both ways)."""
+    t = w.B * w.H * w.N * w.d * 2.0
+    stat = w.B * w.H * w.N * 4.0
+    by = {"fwd": 4 * t + stat, "bwd": 8 * t + 5 * stat}[which]
+    return by / 8e12 * 1e6, by
+
+
+def config_table(rows, cmd):
+    """Text table of per-configuration results (rows: name, workload, ms per step, kernel ms)."""
+    L = ["Fused MHA forward + backward on one MI355X, all benchmark configurations.",
+         "command: %s" % cmd,
+         "TFLOP/s with counted flops (fwd 4*B*H*N^2*d, half if causal; bwd 2.5x); % of the dense fp16/bf16 MFMA peak "
+         "(2.5 PFLOP/s); HBM floor = algorithmic bytes at 8 TB/s; GB/s = algorithmic bytes / measured kernel time.",
+         "fwd and bwd times are kernel times from HIP events on the launch stream (bwd = dQ kernel + dK/dV kernel); "
+         "fwd+bwd is the wall time per step, launch gaps included.",
+         "",
+         "%-4s %-34s | %8s %7s %6s %9s %7s | %8s %7s %6s %9s %7s | %9s %7s %6s" % (
+             "cfg", "B,H,N,d dtype mask", "fwd us", "TFLOP/s", "%peak", "floor us", "GB/s", "bwd us", "TFLOP/s",
+             "%peak", "floor us", "GB/s", "f+b us", "TFLOP/s", "%peak")]
+    for name, w, ms, k in rows:
+        f_us = k["fwd"] * 1e3
+        b_us = (k["bwd_dq"] + k["bwd_dkdv"]) * 1e3
+        ff, fby = hbm_floor_us(w, "fwd")
+        bf, bby = hbm_floor_us(w, "bwd")
+        tf = lambda fl, us: fl / (us * 1e-6) / 1e12
+        L.append("%-4s %-34s | %8.1f %7.1f %6.1f %9.1f %7.0f | %8.1f %7.1f %6.1f %9.1f %7.0f | %9.1f %7.1f %6.1f" % (
+            name, "%d,%d,%d,%d %s %s" % (w.B, w.H, w.N, w.d, w.dtype, "causal" if w.causal else "full"),
+            f_us, tf(w.fwd_flops, f_us), 100 * tf(w.fwd_flops, f_us) / PEAK_TFLOPS, ff, fby / (f_us * 1e-6) / 1e9,
+            b_us, tf(w.bwd_flops, b_us), 100 * tf(w.bwd_flops, b_us) / PEAK_TFLOPS, bf, bby / (b_us * 1e-6) / 1e9,
+            ms * 1e3, tf(w.fwd_flops + w.bwd_flops, ms * 1e3),
+            100 * tf(w.fwd_flops + w.bwd_flops, ms * 1e3) / PEAK_TFLOPS))
+    return "\n".join(L) + "\n"
+
+
 def cpu_baseline(w, budget_s=12.0):
     """Time the fp64 oracle (as it stands) on a bounded sample of heads of the same workload."""
     import oracle
@@ -192,6 +228,8 @@ def main():
                     help="also time the paper's own grid (Sec. 4.1: hidden 2048, d in {64,128}, "
                          "N in {512..16384}, B = 16384/N, both mask settings, fp16, no dropout) "
                          "and add it as an extra field")
+    ap.add_argument("--table", default=None, metavar="FILE",
+                    help="with --all: also write the per-configuration results as a text table to FILE")
     ap.add_argument("--bwd-variants", action="store_true",
                     help="also time the paper's atomic-dQ backward against the default two-kernel backward "
                          "on the workload (extra field)")
@@ -268,6 +306,15 @@ def main():
                             "bwd_tflops": ww.bwd_flops / ((k2["bwd_dq"] + k2["bwd_dkdv"]) * 1e-3) / 1e12,
                             "kernel_ms": {n: v for n, v in k2.items() if not n.startswith("step_")}}
         out["other_configs"] = others
+        if args.table:
+            rows = []
+            for name, ww in synth.WORKLOADS.items():
+                if name == w.name:
+                    rows.append((name, ww, ms, k))
+                else:
+                    rows.append((name, ww, others[name]["ms_per_step"], others[name]["kernel_ms"]))
+            with open(args.table, "w") as f:
+                f.write(config_table(rows, "python3 bench.py " + " ".join(sys.argv[1:])))
     if args.sweep:
         sweep = []
         for d in (64, 128):

@@ -58,6 +58,11 @@ def load_library() -> ctypes.CDLL:
     if library_is_stale():
         from .build import build_library
         build_library()
+    # torch first: its wheel brings its own copy of the HIP runtime, and the streams and pointers this
+    # binding passes belong to that copy.  Loaded after torch, the library binds to the runtime that
+    # is already in the process; loaded before it, it would pull in a second one and every launch
+    # on a torch stream would be refused.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     vp, i, f = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
     lib.spark_mha_fwd.restype = i

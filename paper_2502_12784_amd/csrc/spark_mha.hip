@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
 #include <atomic>
 
 #include "bwd_atomic_kernels.hpp"
@@ -33,6 +35,16 @@ void* static_scratch_ptr() {
   if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
   ptrs[dev].store(p, std::memory_order_release);  // every thread resolves the same address
   return p;
+}
+
+// hipGetLastError() == hipSuccess, and with SPARK_MHA_DEBUG set in the environment the runtime's own
+// description of a failure on stderr (the C ABI itself only returns SPARK_ERR_LAUNCH).
+bool launch_ok(const char* what) {
+  const hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return true;
+  static const bool verbose = getenv("SPARK_MHA_DEBUG") != nullptr;
+  if (verbose) fprintf(stderr, "spark_mha: %s: %s\n", what, hipGetErrorString(e));
+  return false;
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -112,10 +124,14 @@ template <typename KernelT>
 int set_smem(KernelT kernel, int bytes) {
   // The kernels address LDS from 0 (lds_origin): that holds only without static LDS in front.
   hipFuncAttributes fa;
-  if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kernel)) != hipSuccess || fa.sharedSizeBytes != 0)
+  if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kernel)) != hipSuccess || fa.sharedSizeBytes != 0) {
+    if (getenv("SPARK_MHA_DEBUG")) fprintf(stderr, "spark_mha: kernel attributes unavailable or static LDS present\n");
     return SPARK_ERR_LAUNCH;
+  }
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e != hipSuccess && getenv("SPARK_MHA_DEBUG"))
+    fprintf(stderr, "spark_mha: hipFuncSetAttribute(%d bytes of LDS): %s\n", bytes, hipGetErrorString(e));
   return e == hipSuccess ? SPARK_OK : SPARK_ERR_LAUNCH;
 }
 
@@ -158,7 +174,7 @@ int launch_fwd_nw(const Problem& p, const void* Q, const void* K, const void* V,
                      static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
                      static_cast<T*>(O), LSE, p.mq, p.mk, p.mv, p.mo, p.H, p.Nq, p.Nk, p.d, nqt, scale_log2,
                      make_dropout(p.thr, p.seed, p.offset));
-  return hipGetLastError() == hipSuccess ? SPARK_OK : SPARK_ERR_LAUNCH;
+  return launch_ok("forward kernel") ? SPARK_OK : SPARK_ERR_LAUNCH;
 }
 
 template <typename T, int D, bool CAUSAL, bool DROP>
@@ -198,7 +214,7 @@ int launch_bwd(const Problem& p, const void* Q, const void* K, const void* V, co
     hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nqt))), dim3(256), C::SMEM, p.st,
                        q, k, v, o, dout, LSE, Dws, LSE2ws, static_cast<T*>(dQ), p.mq, p.mk, p.mv, p.mo,
                        p.mdo, p.mdq, p.H, p.Nq, p.Nk, p.d, nqt, p.scale, p.scale * 1.4426950408889634f, dr);
-    if (hipGetLastError() != hipSuccess || !mark(1)) return SPARK_ERR_LAUNCH;
+    if (!launch_ok("dQ kernel") || !mark(1)) return SPARK_ERR_LAUNCH;
   }
   {  // dK, dV: one workgroup per tile of 128 keys, software-pipelined
     using C = BwdKvPipeCfg<D>;
@@ -210,7 +226,7 @@ int launch_bwd(const Problem& p, const void* Q, const void* K, const void* V, co
     hipLaunchKernelGGL(kernel, dim3((unsigned)(BH * causal_items<CAUSAL>(nkt))), dim3(256), C::SMEM, p.st,
                        q, k, v, dout, LSE2ws, Dws, static_cast<T*>(dK), static_cast<T*>(dV), p.mq, p.mk,
                        p.mv, p.mdo, p.mdk, p.mdv, p.H, p.Nq, p.Nk, p.d, nkt, p.scale, dr);
-    if (hipGetLastError() != hipSuccess || !mark(2)) return SPARK_ERR_LAUNCH;
+    if (!launch_ok("dK/dV kernel") || !mark(2)) return SPARK_ERR_LAUNCH;
   }
   return SPARK_OK;
 }
