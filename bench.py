@@ -26,15 +26,33 @@ sys.path.insert(0, ROOT)
 PEAK_TFLOPS = 2500.0  # MI355X dense fp16 = bf16 MFMA peak (vendor figure, no sparsity)
 
 
+def csrc_digest() -> str:
+    """SHA-256 over the kernel sources: a counter summary under profiles/ is stamped with the digest
+    of the sources it was measured on, and is only quoted while they are unchanged."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2502_12784_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".hpp")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def read_traffic(workload: str, kernel: str):
-    """HBM bytes per launch measured with rocprofv3 counters, if a summary is committed."""
+    """HBM bytes per launch measured with rocprofv3 counters, if a summary is committed AND was
+    taken on the kernel sources as they are now (its csrc_sha256 line); otherwise None."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
     try:
         with open(path) as f:
-            for line in f:
-                m = re.match(r"\s*%s\s+traffic_bytes_per_launch\s*[:=]\s*([0-9.eE+]+)" % re.escape(kernel), line)
-                if m:
-                    return float(m.group(1))
+            text = f.read()
+        m = re.search(r"csrc_sha256\s*[:=]\s*([0-9a-f]+)", text)
+        if not m or m.group(1) != csrc_digest():
+            return None
+        for line in text.splitlines():
+            m = re.match(r"\s*%s\s+traffic_bytes_per_launch\s*[:=]\s*([0-9.eE+]+)" % re.escape(kernel), line)
+            if m:
+                return float(m.group(1))
     except OSError:
         pass
     return None
@@ -228,6 +246,8 @@ def main():
                     help="also time the paper's own grid (Sec. 4.1: hidden 2048, d in {64,128}, "
                          "N in {512..16384}, B = 16384/N, both mask settings, fp16, no dropout) "
                          "and add it as an extra field")
+    ap.add_argument("--csrc-digest", action="store_true",
+                    help="print the digest of the kernel sources that profiles/hbm_traffic_*.txt are stamped with, and exit")
     ap.add_argument("--table", default=None, metavar="FILE",
                     help="with --all: also write the per-configuration results as a text table to FILE")
     ap.add_argument("--bwd-variants", action="store_true",
@@ -237,6 +257,9 @@ def main():
                     help="also run 5 plain device copies of 256 MiB (reads 256 MiB, writes 256 MiB each) "
                          "so FETCH_SIZE / WRITE_SIZE counters can be scaled against a known size")
     args = ap.parse_args()
+    if args.csrc_digest:
+        print(csrc_digest())
+        return
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (heads shard with no communication); "
                  "--gpus %d is not supported, use --gpus 1" % args.gpus)
