@@ -166,8 +166,28 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
       for (int x = 0; x < 2; ++x) {
         const int o = statA + (sub * 32 + 8 * (2 * half + x)) * 4;
         l[x] = lds_read16<f32x4>(smem, o);
-        d[x] = lds_read16<f32x4>(smem, o + C::BM * 4);
+        if (DROP) d[x] = lds_read16<f32x4>(smem, o + C::BM * 4);
       }
+    };
+    // The workspace holds -D.  Without dropout dS = P o (dP - D) needs no subtraction: the dP
+    // accumulator of a step starts from -D of its 16 query rows instead of from zero (the four
+    // 16-byte reads below deliver them in exactly the accumulator's row order), so the MFMAs
+    // themselves leave dP - D there.  (Under dropout the mask must act on dP alone, so the
+    // accumulator starts from zero and -D is added afterwards.)
+    auto dp_start = [&](int sub) {
+      f32x16 c;
+      if (DROP) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) c[r] = 0.f;
+      } else {
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          const f32x4 v = lds_read16<f32x4>(smem, statA + (sub * 32 + 8 * x) * 4 + C::BM * 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) c[4 * x + e] = v[e];
+        }
+      }
+      return c;
     };
     constexpr int NG = KS / 2;
     constexpr int NTG = 2 * (DT / 2);
@@ -196,10 +216,10 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
         const bool keep = keep_reg(kb, r, dr.thr);
         p[r8] = keep ? pe : 0.f;
         asm volatile("" : "+v"(p[r8]));  // keeps the select in front of the packed conversion
-        ds[r8] = pe * ((keep ? dp[r] : 0.f) - d[r8 >> 2][r8 & 3]);
+        ds[r8] = pe * ((keep ? dp[r] : 0.f) + d[r8 >> 2][r8 & 3]);  // d holds -D (1-p)
       } else {
         p[r8] = pe;
-        ds[r8] = pe * (dp[r] - d[r8 >> 2][r8 & 3]);
+        ds[r8] = pe * dp[r];  // the accumulator started from -D
       }
       // materialise dS here, between the MFMAs around this call: it is not used before the packing
       // at the end of the region, and the compiler would otherwise move its arithmetic there,
@@ -225,7 +245,8 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
     f32x16 sX, dpX, sY, dpY;
     f32x4 lL[2], dL[2], lH[2], dH[2];  // statistics: first half of the next step / second half of the current
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { sX[r] = 0.f; dpX[r] = 0.f; }
+    for (int r = 0; r < 16; ++r) sX[r] = 0.f;
+    dpX = dp_start(0);
     load_agroup(0, 0);
     load_agroup(1, 0);
     load_stats(lL, dL, 0, 0);
@@ -349,7 +370,8 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
 
       // (m, 1) scores  ||  (m, 0) softmax; then (m, 0) dV / dK
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { sY[r] = 0.f; dpY[r] = 0.f; }
+      for (int r = 0; r < 16; ++r) sY[r] = 0.f;
+      dpY = dp_start(1);  // statA points at stage m here
       auto request_B = [&](int part) {
         if (part != 1) point_A(slot1);  // stage m+1 has been resident since the end of stage m-1
         if (part != 1) load_agroup(0, 0);
@@ -364,8 +386,9 @@ __global__ __launch_bounds__(256, (D == 64 && !DROP) ? 2 : 1) void mha_bwd_dkdv_
       step(sY, dpY, 1, m * C::BM + 32, sX, dpX, 0, m * C::BM, request_B);
       // (m+1, 0) scores  ||  (m, 1) softmax; then (m, 1) dV / dK
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { sX[r] = 0.f; dpX[r] = 0.f; }
+      for (int r = 0; r < 16; ++r) sX[r] = 0.f;
       if (!EARLY) request_B(2);
+      dpX = dp_start(0);  // statA points at stage m + 1 by now (request_B moved it)
       sched_fence();
       step(sX, dpX, 0, (m + 1) * C::BM, sY, dpY, 1, m * C::BM + 32, request_A);
 
@@ -496,12 +519,21 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
     Dq = half_pair_sum(Dq) * (DROP ? dr.keep_prob : 1.0f);
     lse2 *= 1.4426950408889634f;
     if (g == 0 && qrow < Nq) {
-      Dout[(size_t)head * Nq + qrow] = Dq;
+      Dout[(size_t)head * Nq + qrow] = -Dq;  // negated: the dK/dV kernel starts its dP accumulators from it
       LSE2out[(size_t)head * Nq + qrow] = lse2;
     }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks]), "+v"(dof[ks]));
     asm volatile("" : "+v"(lse2), "+v"(Dq));
+    // Without dropout dS = P o (dP - D) needs no subtraction: every dP accumulator starts from -D
+    // (one value per lane here: lane = query), handed to the first MFMA as its addend.  That costs 16
+    // registers for the whole loop; at D = 128 the kernel has none to spare (the causal one would
+    // spill, measured +4 %), so only D = 64 does it (dQ kernel -2 ... -3 %).
+    constexpr bool FOLD_D = !DROP && D == 64;
+    f32x16 dneg;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dneg[r] = -Dq;
+    if (FOLD_D) asm volatile("" : "+v"(dneg));
     __syncthreads();
 
     // One iteration, compiled twice: MASKED for tiles that the diagonal or the end of the keys
@@ -526,9 +558,11 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
         constexpr int MT = C::BN / 32;  // 32-key blocks per tile
         f32x16 s[MT], dp[MT];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+        for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) { s[mt][r] = 0.f; dp[mt][r] = 0.f; }
+          if (FOLD_D) dp[mt] = dneg;
+        }
         constexpr int AHEAD = 4;
         v8 fa[AHEAD][MT];
         auto load_step = [&](int i) {
@@ -597,8 +631,12 @@ __global__ __launch_bounds__(256, 2) void mha_bwd_dq_kernel(
         float ds[16 * MT];
         auto ds_elem = [&](int e) {
           const int mt = e / 16, r = e % 16;
-          const float dpe = DROP && !keep_reg(keep[mt], r, dr.thr) ? 0.f : dp[mt][r];
-          ds[e] = pe[e] * (dpe - Dq);
+          if (FOLD_D) {
+            ds[e] = pe[e] * dp[mt][r];  // the accumulator started from -D
+          } else {
+            const float dpe = DROP && !keep_reg(keep[mt], r, dr.thr) ? 0.f : dp[mt][r];
+            ds[e] = pe[e] * (dpe - Dq);
+          }
           asm volatile("" : "+v"(ds[e]));
         };
         // dQ^T += K^T dS^T, 16 keys per step; step kk uses elements 8 kk .. 8 kk + 7.  Those of
