@@ -103,6 +103,34 @@ def test_static_workspace_entry_point_validation(lib):
     assert call(B=2, H=8, N=(rows // 16) + 1) == E_WS   # one row too many for the fixed scratch array
 
 
+def test_atomic_backward_validation(lib):
+    """spark_mha_bwd_atomic: same refusals as the default backward, and its own workspace size."""
+    def call(ws=0xA000, ws_bytes=1 << 30, dq=0x7000, Nq=128, Nk=96, d=64, causal=0, dtype=0):
+        return lib.spark_mha_bwd_atomic(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, dq, 0x8000, 0x9000,
+                                        ws, ws_bytes, 1, 2, Nq, Nk, d, 0.125, causal, dtype, None)
+    need = pkg.spark_mha_bwd_atomic_workspace_bytes(1, 2, 128, 96, 64, 0)
+    assert need == 2 * 2 * 128 * 4 + 2 * 128 * 64 * 4   # statistics (already a multiple of 256) + fp32 dQ
+    assert pkg.spark_mha_bwd_atomic_workspace_bytes(1, 2, 100, 96, 64, 0) == 1792 + 2 * 100 * 64 * 4  # padded to 256
+    assert pkg.spark_mha_bwd_atomic_workspace_bytes(1, 2, 128, 96, 100, 0) == 0
+    assert call(ws=None) == E_NULL
+    assert call(dq=None) == E_NULL
+    assert call(d=100) == E_SHAPE
+    assert call(causal=1) == E_SHAPE            # causal needs Nq == Nk
+    assert call(dtype=9) == E_DTYPE
+    assert call(dq=0x7008) == E_ALIGN
+    assert call(ws_bytes=need - 1) == E_WS
+
+
+def test_dropout_marked_validation(lib):
+    def call(events, p=0.1):
+        return lib.spark_mha_dropout_bwd_marked(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000, 0x8000,
+                                                0x9000, 0xA000, 1 << 20, 1, 1, 128, 128, 64, 0.125, 0, p, 1234, 0,
+                                                0, None, events)
+    assert call(None) == E_NULL
+    assert call((ctypes.c_void_p * 3)(1, 2, None)) == E_NULL
+    assert call((ctypes.c_void_p * 3)(1, 2, 3), p=1.5) == E_SHAPE
+
+
 def test_cross_validation(lib):
     def fwd(Nq=128, Nk=96, causal=0, **kw):
         a = dict(q=0x1000, k=0x2000, v=0x3000, o=0x4000, lse=0x5000, B=1, H=1, d=64, scale=0.125, dtype=0)

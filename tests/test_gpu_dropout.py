@@ -121,3 +121,22 @@ def test_dropout_full_size_configs_sampled_heads(name):
     pu.assert_within_tolerance(m, name)
     for n in ("O", "LSE", "dQ", "dK", "dV"):
         assert np.isfinite(pu.to_f64(gpu[n])).all(), n
+
+
+def test_marked_dropout_backward_is_the_same_work():
+    """spark_mha_dropout_bwd_marked: identical gradients, and its three events are ordered in time."""
+    import torch
+    from paper_2502_12784_amd import HipEvents, spark_mha_dropout_bwd, spark_mha_dropout_fwd
+    B, H, N, d, dtype = 2, 3, 700, 128, synth.BF16
+    inp = synth.make_inputs(B, H, N, d, dtype, seed=6500)
+    Q, K, V, dO = (pu.to_device(inp[n], dtype) for n in ("Q", "K", "V", "dO"))
+    drop = (0.1, SEED, 9)
+    O, LSE = spark_mha_dropout_fwd(Q, K, V, 0.1, True, *drop)
+    want = spark_mha_dropout_bwd(Q, K, V, O, LSE, dO, 0.1, True, *drop)
+    ev = HipEvents(3)
+    got = spark_mha_dropout_bwd(Q, K, V, O, LSE, dO, 0.1, True, *drop, events=(ev, 0))
+    torch.cuda.synchronize()
+    for a, b, n in zip(got, want, ("dQ", "dK", "dV")):
+        assert torch.equal(a, b), n
+    assert ev.elapsed_ms(0, 1) > 0 and ev.elapsed_ms(1, 2) > 0
+    ev.close()
