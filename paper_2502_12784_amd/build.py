@@ -30,6 +30,21 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+MIX_BENCH = os.path.join(HERE, "mix_floor_bench")
+
+
+def build_mix_floor_bench() -> str:
+    """The stand-alone microbenchmark csrc/mix_floor_bench.hip (what the instruction mix of each
+    attention loop costs as a straight-line loop on this GPU); run the executable on the GPU."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
+    res = subprocess.run([hipcc] + flags + [os.path.join(CSRC, "mix_floor_bench.hip"), "-o", MIX_BENCH],
+                         stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout)
+    return MIX_BENCH
+
+
 def kernel_resources() -> str:
     """Registers, scratch and occupancy of every kernel instantiation, from the compiler's own
     resource-usage remarks (device compilation only, nothing is written next to the sources)."""
@@ -96,5 +111,7 @@ if __name__ == "__main__":
     import sys
     if "--resources" in sys.argv:
         print(kernel_resources(), end="")
+    elif "--mix-bench" in sys.argv:
+        print(build_mix_floor_bench())
     else:
         print(build_library(verbose=True))
