@@ -27,13 +27,14 @@ PEAK_TFLOPS = 2500.0  # MI355X dense fp16 = bf16 MFMA peak (vendor figure, no sp
 
 
 def csrc_digest() -> str:
-    """SHA-256 over the kernel sources: a counter summary under profiles/ is stamped with the digest
-    of the sources it was measured on, and is only quoted while they are unchanged."""
+    """SHA-256 over the library's kernel sources (spark_mha.hip and the headers it is built from): a
+    counter summary under profiles/ is stamped with the digest of the sources it was measured on,
+    and is only quoted while they are unchanged."""
     import hashlib
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2502_12784_amd", "csrc")
     for name in sorted(os.listdir(csrc)):
-        if name.endswith((".hip", ".hpp")):
+        if name.endswith(".hpp") or name == "spark_mha.hip":
             h.update(name.encode())
             h.update(open(os.path.join(csrc, name), "rb").read())
     return h.hexdigest()[:16]
