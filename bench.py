@@ -59,9 +59,15 @@ def read_traffic(workload: str, kernel: str):
     return None
 
 
-def time_workload(w, steps, warmup, dropout=None):
+def time_workload(w, steps, warmup, dropout=None, check_seconds=0.0):
     """Average ms per step (wall clock) and per kernel (HIP events on the launch stream).
-    dropout: None, or (p_drop, seed, offset): the dropout entry points."""
+    dropout: None, or (p_drop, seed, offset): the dropout entry points.
+    check_seconds > 0: before the warm-up steps, the path that is about to be timed is run repeatedly
+    for that long and checked: outputs finite, bit-identical from the first run to the last (the
+    default backward has no atomics), columns of dK summing to zero over the keys and
+    sum_j dV_j = sum_i dO_i (rows of P sum to one).  The result is returned under "self_check"; a
+    benchmark of a path that fails it is refused.  (These runs are not part of the warm-up count,
+    and they also bring the part to its sustained clock; their number is reported.)"""
     import torch
     from paper_2502_12784_amd import (HipEvents, spark_mha_bwd, spark_mha_dropout_bwd,
                                       spark_mha_dropout_fwd, spark_mha_fwd, synth)
@@ -92,6 +98,28 @@ def time_workload(w, steps, warmup, dropout=None):
             spark_mha_dropout_bwd(Q, K, V, O, LSE, dO, w.scale, w.causal, *dropout, dQ=dQ, dK=dK,
                                   dV=dV, workspace=ws, events=None if ev is None else (ev, base + 1))
 
+    check = None
+    if check_seconds > 0:
+        step()
+        torch.cuda.synchronize()
+        first = [t.clone() for t in (O, LSE, dQ, dK, dV)]
+        n, t0 = 1, time.perf_counter()
+        while time.perf_counter() - t0 < check_seconds:
+            for _ in range(10):
+                step()
+            torch.cuda.synchronize()
+            n += 10
+        stable = all(torch.equal(a, b) for a, b in zip(first, (O, LSE, dQ, dK, dV)))
+        finite = all(bool(torch.isfinite(t.float()).all()) for t in (O, LSE, dQ, dK, dV))
+        dk_sum = dK.double().sum(2).abs().max().item() / max(dK.double().abs().sum(2).max().item(), 1e-30)
+        dv_gap = ((dV.double().sum(2) - dO.double().sum(2)).abs().max().item()
+                  / max(dO.double().abs().sum(2).max().item(), 1e-30))
+        check = {"steps": n, "seconds": time.perf_counter() - t0, "bitwise_stable": stable, "finite": finite,
+                 "dK_column_sum_rel": dk_sum, "dV_minus_dO_column_sum_rel": dv_gap,
+                 "ok": bool(stable and finite and dk_sum <= 2e-2 and dv_gap <= 2e-2)}
+        del first
+        if not check["ok"]:
+            sys.exit("bench.py: the path to be timed fails its self-check: %s" % json.dumps(check))
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
@@ -115,6 +143,8 @@ def time_workload(w, steps, warmup, dropout=None):
     k = {n: v / steps for n, v in k.items()}
     k["step_median"] = per_step[len(per_step) // 2]
     k["step_min"] = per_step[0]
+    if check is not None:
+        k["step_self_check"] = check
     return wall / steps * 1e3, k
 
 
@@ -269,11 +299,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="C4", help="C1..C5 (default C4: N=4096, d=128, bf16, causal)")
     ap.add_argument("--all", action="store_true", help="also time the other four configs (extra field)")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg and the extra run with dropout (profiling runs)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg, the self-check and the extra run with dropout (profiling runs)")
     ap.add_argument("--sweep", action="store_true",
                     help="also time the paper's own grid (Sec. 4.1: hidden 2048, d in {64,128}, "
                          "N in {512..16384}, B = 16384/N, both mask settings, fp16, no dropout) "
                          "and add it as an extra field")
+    ap.add_argument("--no-check", action="store_true",
+                    help="skip the self-check of the timed path (0.3 s of repeated steps before the warm-up steps)")
     ap.add_argument("--csrc-digest", action="store_true",
                     help="print the digest of the kernel sources that profiles/hbm_traffic_*.txt are stamped with, and exit")
     ap.add_argument("--table", default=None, metavar="FILE",
@@ -307,7 +339,7 @@ def main():
         del src, dst
 
     w = synth.WORKLOADS[args.workload]
-    ms, k = time_workload(w, args.steps, args.warmup)
+    ms, k = time_workload(w, args.steps, args.warmup, check_seconds=0.0 if (args.no_check or args.no_cpu) else 0.3)
     flops_step = w.fwd_flops + w.bwd_flops
     value = flops_step / (ms * 1e-3) / 1e12
 
@@ -330,6 +362,7 @@ def main():
         "bwd_tflops": w.bwd_flops / ((k["bwd_dq"] + k["bwd_dkdv"]) * 1e-3) / 1e12,
         "kernel_ms": {n: v for n, v in k.items() if not n.startswith("step_")},
         "ms_per_step_median": k["step_median"], "ms_per_step_min": k["step_min"],
+        "self_check": k.get("step_self_check"),
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_TFLOPS,
                      "traffic": read_traffic(w.name, dom)},
