@@ -45,10 +45,9 @@ def build_mix_floor_bench() -> str:
     return MIX_BENCH
 
 
-def kernel_resources() -> str:
-    """Registers, scratch and occupancy of every kernel instantiation, from the compiler's own
-    resource-usage remarks (device compilation only, nothing is written next to the sources)."""
-    import re
+def device_assembly():
+    """(assembly text, compiler remarks) of the library's device code; nothing is written next to
+    the sources."""
     import tempfile
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
@@ -58,7 +57,27 @@ def kernel_resources() -> str:
                              stderr=subprocess.STDOUT, text=True)
         if res.returncode != 0:
             raise RuntimeError("hipcc failed:\n" + res.stdout)
-        asm = open(os.path.join(tmp, "out.s")).read()
+        return open(os.path.join(tmp, "out.s")).read(), res.stdout
+
+
+def unguarded_lds_loads(asm: str):
+    """Direct global->LDS loads in the assembly that are not immediately preceded by the s_nop 4 hazard
+    guard (see BufView::load16_to_lds): the compiler cannot see those loads, so nothing else
+    separates them from a VALU write of the scalar registers they read.  Returns the offending lines."""
+    import re
+    lines = [l.strip() for l in asm.split("\n") if l.startswith("\t") and not l.strip().startswith((".", ";"))]
+    return [l for prev, l in zip(lines, lines[1:])
+            if re.match(r"buffer_load_dword(x4)? .* lds", l) and prev != "s_nop 4"]
+
+
+def kernel_resources() -> str:
+    """Registers, scratch and occupancy of every kernel instantiation, from the compiler's own
+    resource-usage remarks."""
+    import re
+    asm, remarks = device_assembly()
+
+    class res:  # noqa: N801  (keeps the parsing below unchanged)
+        stdout = remarks
     rows = []
     for block in re.split(r"remark: Function Name: ", res.stdout)[1:]:
         mangled = block.split()[0]

