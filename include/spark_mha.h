@@ -88,7 +88,7 @@ int spark_mha_fwd(const void* Q, const void* K, const void* V, void* O, float* L
 
 /*
  * Bytes of device workspace spark_mha_bwd needs for this problem (holds
- * D = rowsum(dO o O) and LSE * log2(e), fp32 [B,H,N] each).  Returns 0 for invalid shapes.
+ * -D, D = rowsum(dO o O), and LSE * log2(e), fp32 [B,H,N] each).  Returns 0 for invalid shapes.
  */
 size_t spark_mha_bwd_workspace_bytes(int B, int H, int N, int d, spark_dtype_t dtype);
 
